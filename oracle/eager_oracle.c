@@ -1,0 +1,123 @@
+/*
+ * CPU oracle for the eager-SGD hot path: one partial-allreduce round with stale-gradient
+ * carry, averaged over P and applied as a momentum-SGD update.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU library is
+ * checked against.  It shares no code with the GPU library and must never be called
+ * from the product path; only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may use it.
+ *
+ * What it follows (paper: "Taming Unbalanced Training Workloads in Deep Learning with
+ * Partial Collective Operations"):
+ *   - Section 5, the two-process walk-through of Fig. 7: a process that is late at round
+ *     t contributes only what its send buffer holds (nothing, or the gradient it finished
+ *     late in the previous round); the gradient it finishes late becomes the new content
+ *     of the send buffer; a process that is on time contributes send buffer + fresh
+ *     gradient and its send buffer becomes empty (G_null).
+ *   - Algorithm 2, line 6: the result is the sum of the contributions times 1/P (P, not
+ *     the number of contributors); lines 7-8: the update rule U is applied to it.
+ *   - Section 6.1: the per-process bit s_t^i "my update was included" is the
+ *     participation mask; a rejected update is added in the next round, exactly once.
+ *
+ * Readings where the paper is silent (they are conventions of this repository):
+ *   - U is heavy-ball momentum SGD, v <- mu*v + u, w <- w - lr*v, each as one fused
+ *     multiply-add (single rounding); no Nesterov, no weight decay.
+ *   - fp32 throughout, round-to-nearest-even; the P contributions are added in
+ *     ascending rank order starting from +0.0f; 1/P is computed once in fp32 and
+ *     multiplied.  This fixed order is what makes a bit-exact comparison possible.
+ *     "parity unpinned" for the ORDER itself: the paper fixes no order, so nothing
+ *     outside this repository can confirm it; every value-level property is pinned by
+ *     the tests (brute-force ledger, worked example, allreduce special case,
+ *     conservation, Lemma-2 identity, closed-form momentum).
+ *
+ * Compile with -ffp-contract=off so that no multiply-add is fused except where fmaf is
+ * written out.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+static inline float widen_bf16(uint16_t h)
+{
+    uint32_t b = (uint32_t)h << 16;   /* bf16 is the top half of an fp32: exact */
+    float f;
+    memcpy(&f, &b, sizeof f);
+    return f;
+}
+
+/*
+ * One round over one bucket of n elements.
+ *
+ *   P            number of processes (1..64)
+ *   G[p]         fresh gradient of process p, n elements, fp32 or bf16 (grad_is_bf16)
+ *   R[p]         send buffer of process p (fp32, n elements); read only where bit p of
+ *                `valid` is set, written for every process whose bit in `mask` is clear
+ *   valid        bit p set: R[p] holds a gradient that has not been delivered yet
+ *   mask         bit p set: process p is active in this round (s_t^p = true)
+ *   w, v         parameters and momentum (fp32, n elements), updated in place; both may
+ *                be NULL to skip the update rule
+ *   recv         receive buffer, gets the averaged result u; may be NULL
+ *   nthreads     1 = the scalar reference; >1 = same loop body, elements partitioned
+ *                statically over threads (per-element arithmetic and order unchanged)
+ *
+ * After the call the caller sets valid' = ~mask (on-time processes emptied their send
+ * buffer, late ones stored the gradient they finished late).
+ */
+void eager_oracle_round(int P, int64_t n,
+                        const void *const *G, int grad_is_bf16,
+                        float *const *R, uint64_t valid, uint64_t mask,
+                        float *w, float *v, float lr, float mu,
+                        float *recv, int nthreads)
+{
+    const float inv_P = 1.0f / (float)P;
+    int64_t i;
+    (void)nthreads;
+#pragma omp parallel for schedule(static) num_threads(nthreads) if (nthreads > 1)
+    for (i = 0; i < n; ++i) {
+        float s = 0.0f;
+        int p;
+        for (p = 0; p < P; ++p) {
+            const float g = grad_is_bf16 ? widen_bf16(((const uint16_t *)G[p])[i])
+                                         : ((const float *)G[p])[i];
+            const int on_time = (int)((mask >> p) & 1u);
+            const int has_stale = (int)((valid >> p) & 1u);
+            if (on_time) {
+                /* contributes stale + fresh; its send buffer becomes G_null */
+                float c = g;
+                if (has_stale)
+                    c = R[p][i] + g;
+                s = s + c;
+            } else {
+                /* contributes only what was pending; the late gradient is stored */
+                if (has_stale)
+                    s = s + R[p][i];
+                R[p][i] = g;
+            }
+        }
+        {
+            const float u = s * inv_P;
+            if (w) {
+                const float vn = fmaf(mu, v[i], u);
+                v[i] = vn;
+                w[i] = fmaf(-lr, vn, w[i]);
+            }
+            if (recv)
+                recv[i] = u;
+        }
+    }
+}
+
+/* The update rule alone, applied to an already averaged result u (the unfused path:
+ * receive buffer first, optimizer afterwards). */
+void eager_oracle_sgd(int64_t n, const float *u, float *w, float *v, float lr, float mu,
+                      int nthreads)
+{
+    int64_t i;
+    (void)nthreads;
+#pragma omp parallel for schedule(static) num_threads(nthreads) if (nthreads > 1)
+    for (i = 0; i < n; ++i) {
+        const float vn = fmaf(mu, v[i], u[i]);
+        v[i] = vn;
+        w[i] = fmaf(-lr, vn, w[i]);
+    }
+}
