@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Throughput of the fused eager-SGD round (partial allreduce + carry + momentum SGD) on
+one MI355X, on synthetic gradients shaped like the paper's workloads.
+
+A step = plan participation from that step's seeded compute times (host) + one fused
+round over every bucket of the model (device).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line (see README / DESIGN for the fields).
+
+  python bench.py [--steps K] [--warmup W] [--config 2] [--order fixed|fast]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+PAPER_CONTEXT = ("paper (Piz Daint, Xeon E5-2690 + P100 per node, Cray Aries, fp32): eager-SGD "
+                 "1.29x over Deep500 / 1.27x over Horovod (ResNet-50, 64 proc), 1.27x over "
+                 "Horovod (LSTM/UCF101, majority), 2.64x over async PS; end-to-end training "
+                 "throughput on a cluster, not this kernel: context only")
+
+
+def alg_bytes_per_element(P: int, gbytes: int, q_prev: int, q_now: int) -> int:
+    """Algorithmic HBM bytes per element of one round: every fresh gradient read once,
+    non-empty send buffers read, send buffers of late processes written, w and v read and
+    written.  Empty send buffers and the reset of on-time ones cost nothing."""
+    return gbytes * P + 4 * q_prev + 4 * q_now + 16
+
+
+def popcount(x: int) -> int:
+    return bin(x).count("1")
+
+
+class Workload:
+    """Device state of one configuration, inputs generated on the GPU by the seeded
+    generator (outside any timed region)."""
+
+    def __init__(self, k: int, order: str, launch: dict | None = None, stagger: int = 0):
+        import torch
+        from paper_1908_04207_amd import binding as eb
+        from workloads import grads as wg
+        from workloads import shapes
+        self.torch, self.eb = torch, eb
+        self.cfg = cfg = shapes.config(k)
+        bt = cfg.buckets
+        dev = torch.device("cuda:0")
+        self.gdtype = torch.bfloat16 if cfg.grad_dtype == "bf16" else torch.float32
+        self.gbytes = 2 if cfg.grad_dtype == "bf16" else 4
+        self.ctx = eb.Context(cfg.P, bt.offset, bt.numel,
+                              eb.BF16 if cfg.grad_dtype == "bf16" else eb.F32,
+                              eb.ORDER_FIXED if order == "fixed" else eb.ORDER_FAST)
+        for key, val in (launch or {}).items():
+            self.ctx.eager_set_launch(key, val)
+        n = bt.arena_numel
+
+        def arena(dtype, i):
+            # optional stagger: shifts each stream's base by i*stagger bytes so that the
+            # P same-offset streams do not start on the same HBM channel
+            pad = (i * stagger) // (2 if dtype == torch.bfloat16 else 4)
+            return torch.empty(n + pad, dtype=dtype, device=dev)[pad:]
+        self.G = [arena(self.gdtype, p) for p in range(cfg.P)]
+        self.R = [arena(torch.float32, cfg.P + p) for p in range(cfg.P)]
+        for p in range(cfg.P):
+            wg.fill(self.G[p], cfg.seed, 0, p, cfg.grad_sigma)
+            self.R[p].zero_()
+        self.w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
+        self.v = torch.zeros(n, device=dev)
+        self.step_no = 0
+        self.q_prev = 0
+        torch.cuda.synchronize()
+
+    def plan(self, step: int):
+        from workloads import times
+        cfg, eb = self.cfg, self.eb
+        t = times.compute_times(cfg.times, cfg.P, cfg.seed, step)
+        return eb.eager_plan_participation(eb.SOLO if cfg.mode == "solo" else eb.MAJORITY, t,
+                                           cfg.seed, step)
+
+    def step(self) -> int:
+        """One step; returns its algorithmic bytes."""
+        cfg = self.cfg
+        plan = self.plan(self.step_no)
+        self.ctx.eager_partial_allreduce(plan, self.G, self.R, recv=None,
+                                         opt=(self.w, self.v, cfg.lr, cfg.mu))
+        q_now = cfg.P - plan.nap
+        b = alg_bytes_per_element(cfg.P, self.gbytes, self.q_prev, q_now) * cfg.numel
+        self.q_prev = q_now
+        self.step_no += 1
+        return b
+
+
+def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0,
+            per_step_events=True):
+    import torch
+    wl = Workload(k, order, launch, stagger)
+    for _ in range(warmup):
+        wl.step()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)] if per_step_events else None
+    nbytes = []
+    t0 = time.perf_counter()
+    for i in range(steps):
+        if ev:
+            ev[i][0].record()
+        nbytes.append(wl.step())
+        if ev:
+            ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [a.elapsed_time(b) for a, b in ev] if ev else []
+    return wl, wall, nbytes, kern_ms
+
+
+def copy_ceiling_gbs() -> dict:
+    """Device-to-device copy and read-only stream rates of plain kernels, for context."""
+    import torch
+    from paper_1908_04207_amd import binding as eb
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty(n, dtype=torch.uint8, device="cuda")
+    a.zero_()
+    sink = torch.zeros(1, device="cuda")
+    out = {}
+    for name, fn, traffic in (("copy", lambda: eb.eager_calib_copy(b, a, n), 2 * n),
+                              ("read", lambda: eb.eager_calib_read(a, n, sink), n)):
+        for _ in range(3):
+            fn()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(10):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        out[name] = traffic * 10 / (s.elapsed_time(e) * 1e-3) / 1e9
+    return out
+
+
+def cpu_baseline(wl: Workload, budget_s: float = 20.0) -> dict:
+    """The CPU oracle, as it stands, on this host's cores, on a bounded sample of the
+    same workload: the first rounds of the configuration on a leading slice of the arena
+    (whole buckets), same gradients and plans as the GPU run."""
+    import numpy as np
+    from oracle import eager_oracle as eo
+    cfg = wl.cfg
+    bt = cfg.buckets
+    cores = len(os.sched_getaffinity(0))
+    # leading buckets up to ~4M elements per process keep the sample to seconds
+    nb, tot = 0, 0
+    while nb < bt.n_buckets and (nb == 0 or tot + bt.numel[nb] <= (1 << 22)):
+        tot += bt.numel[nb]
+        nb += 1
+    hi = bt.offset[nb - 1] + bt.numel[nb - 1]
+    if bt.numel[0] > (1 << 22):              # a single huge first bucket: take a slice of it
+        hi, tot = 1 << 22, 1 << 22
+        offs, nums = [0], [hi]
+    else:
+        offs, nums = list(bt.offset[:nb]), list(bt.numel[:nb])
+
+    def host(t):
+        t = t[:hi].cpu()
+        if t.dtype == wl.torch.bfloat16:
+            return t.view(wl.torch.int16).numpy().view(np.uint16)
+        return t.numpy()
+    import torch
+    from workloads import grads as wg
+    G = [host(g) for g in wl.G]
+    w0 = wg.fill(torch.empty(hi), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma).numpy()
+    res = {}
+    for label, nthreads in (("threaded", cores), ("scalar", 1)):
+        st = eo.OracleState(cfg.P, offs, nums, hi, w0, cfg.lr, cfg.mu)
+        q_prev, nbytes, secs, rounds = 0, 0, 0.0, 0
+        limit = budget_s * (0.6 if nthreads > 1 else 0.4)
+        for step in range(cfg.steps):
+            mask = wl.plan(step).mask
+            t0 = time.perf_counter()
+            st.round(mask, G, nthreads=nthreads)
+            secs += time.perf_counter() - t0
+            q_now = cfg.P - popcount(mask)
+            nbytes += alg_bytes_per_element(cfg.P, wl.gbytes, q_prev, q_now) * tot
+            q_prev = q_now
+            rounds += 1
+            if secs > limit:
+                break
+        res[label] = (nbytes / secs / 1e9, rounds, secs)
+    gbs, rounds, secs = res["threaded"]
+    return {"value": round(gbs, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{rounds} rounds of {cfg.name} on its first {tot} elements per process "
+                      f"({len(nums)} buckets), element-parallel oracle, {secs:.1f} s",
+            "scalar_1core_GBs": round(res["scalar"][0], 3)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--order", choices=("fixed", "fast"), default="fixed")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceiling", action="store_true")
+    ap.add_argument("--launch", default="", help="key=value,... passed to eager_set_launch")
+    ap.add_argument("--stagger", type=int, default=0, help="bytes of base offset per stream")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (P simulated processes share its HBM); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
+    wl, wall, nbytes, kern_ms = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger)
+    cfg = wl.cfg
+    total_b = sum(nbytes)
+    kern_s = sum(kern_ms) * 1e-3
+    achieved = total_b / kern_s / 1e9
+    out = {
+        "metric": "effective reduce+update GB/s (fused partial allreduce + momentum SGD)",
+        "value": round(total_b / wall / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(wall / a.steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.grad_dtype == "f32" else "bf16 gradients, f32 accumulation/state",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode,
+                   "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
+                   "order": a.order, "launch": launch, "stagger": a.stagger},
+        "steps_per_s": round(a.steps / wall, 2),
+        "pct_hbm_peak": round(100.0 * total_b / wall / 1e9 / HBM_PEAK_GBS, 2),
+        "alg_bytes_per_step": round(total_b / a.steps),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "kernel": "round_kernel",
+                     "avg_kernel_ms": round(kern_s / a.steps * 1e3, 5)},
+        "paper_context": PAPER_CONTEXT,
+    }
+    if not a.no_ceiling:
+        c = copy_ceiling_gbs()
+        out["measured_ceiling_GBs"] = {"copy_read_plus_write": round(c["copy"], 1),
+                                       "read_only": round(c["read"], 1)}
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

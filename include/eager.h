@@ -1,0 +1,177 @@
+/*
+ * eager.h - C ABI of the eager-SGD hot path on one MI355X (gfx950).
+ *
+ * What the library computes (paper: "Taming Unbalanced Training Workloads in Deep
+ * Learning with Partial Collective Operations", PPoPP'20):
+ *
+ *   P processes train data-parallel.  Each round every process owns a fresh gradient
+ *   G_p and a send buffer R_p that is either empty (G_null) or holds the gradient the
+ *   process finished too late for the previous round (Section 5, walk-through of
+ *   Fig. 7).  A partial allreduce (Section 4) does not wait for everybody: processes
+ *   that are on time ("active", Section 7.1) contribute R_p + G_p and end with an empty
+ *   send buffer; late ("passive") processes contribute only R_p, and the gradient they
+ *   finish late becomes the new R_p.  The sum of the contributions is scaled by 1/P
+ *   (Algorithm 2, line 6) and handed to the update rule U (Algorithm 2, lines 7-8),
+ *   here heavy-ball momentum SGD:  v <- mu*v + u ;  w <- w - lr*v.
+ *
+ *   All P processes are simulated on one GPU: their gradient and send buffers are
+ *   P device arrays, and one kernel pass per round does reduce + carry + update.
+ *
+ * Conventions
+ *   - Every function returns an eager_status; no exception crosses the boundary.
+ *   - "device" pointers are HIP device memory owned by the caller; the library never
+ *     allocates, frees or clears them.  "host" pointers are ordinary host memory.
+ *   - Kernels are enqueued on the caller's stream (a hipStream_t passed as void*,
+ *     NULL = the default stream).  No call synchronises the device.
+ *   - Arena layout: each of G_p, R_p, w, v, recv is one flat array per process in
+ *     which bucket b occupies elements [bucket_offset[b], bucket_offset[b] +
+ *     bucket_numel[b]).  Bucket starts are multiples of 16 bytes of the gradient type
+ *     (4 fp32 / 8 bf16 elements).  Elements between consecutive buckets of one call's
+ *     range are padding that the library may read and overwrite; they carry no data.
+ *   - A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef EAGER_H
+#define EAGER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct eager_ctx eager_ctx;   /* opaque: bucket table, send-buffer validity, last error */
+
+typedef enum { EAGER_SOLO = 0, EAGER_MAJORITY = 1 } eager_mode;
+typedef enum { EAGER_F32 = 0, EAGER_BF16 = 1 } eager_dtype;          /* type of G only */
+typedef enum { EAGER_ORDER_FIXED = 0, EAGER_ORDER_FAST = 1 } eager_order;
+
+typedef enum {
+    EAGER_OK = 0,
+    EAGER_EINVAL = 1,    /* bad argument: NULL, P outside 1..64, misaligned pointer, empty range */
+    EAGER_ESHAPE = 2,    /* bucket table malformed (overlap, misaligned start, negative size)    */
+    EAGER_ESTATE = 3,    /* plan does not fit the context or the entry point, or a bucket is
+                            given the same round twice                                           */
+    EAGER_EDEVICE = 4,   /* a HIP call or a kernel launch failed                                 */
+    EAGER_ENOMEM = 5     /* host allocation failed                                               */
+} eager_status;
+
+#define EAGER_MAX_P 64
+#define EAGER_FLAG_STRICT_QUORUM 1u
+
+/* Participation of one round: bit p of `mask` is the response bit s_t^p of Section 6.1
+ * ("my update was included").  nap = number of active processes (Section 7.1). */
+typedef struct {
+    int32_t  mode;        /* eager_mode */
+    int32_t  P;
+    uint64_t step;        /* round index t */
+    uint64_t mask;
+    int32_t  initiator;   /* rank that triggered the round */
+    int32_t  nap;         /* popcount(mask) >= 1 (Lemma 1, quorum size) */
+} eager_plan;
+
+/* Update rule U of Algorithm 2, lines 7-8: momentum SGD.  params/momentum are device
+ * arena base pointers (fp32, 16-byte aligned), updated in place. */
+typedef struct {
+    float *params;
+    float *momentum;
+    float  lr;
+    float  mu;
+} eager_opt;
+
+/*
+ * Create a context for P processes and n_buckets layer-wise buckets (Section 3: one
+ * reduction per layer, possibly fused).  bucket_offset / bucket_numel: host arrays of
+ * n_buckets element counts, copied.  Buckets must be ascending and disjoint, starts
+ * aligned as described above.  All send buffers start empty.
+ *   order FIXED: contributions are added in ascending rank order starting from +0.0f,
+ *                1/P is one fp32 multiplication, the update rule is two fused
+ *                multiply-adds - results are reproducible bit for bit.
+ *   order FAST : the library may reassociate the sum and contract multiply-adds.
+ * Errors: EINVAL (NULL, P, n_buckets < 1, unknown dtype/order), ESHAPE, ENOMEM.
+ */
+int eager_create(eager_ctx **out, int P, int n_buckets, const int64_t *bucket_offset,
+                 const int64_t *bucket_numel, int grad_dtype, int order);
+int eager_destroy(eager_ctx *ctx);                 /* NULL is allowed */
+
+/* Text of the last error of this context (owned by the context, valid until its next
+ * call); eager_status_string names a status code (static storage). */
+const char *eager_last_error(const eager_ctx *ctx);
+const char *eager_status_string(int status);
+
+/*
+ * Decide who is active in round `step` from the times (ms, host array of P doubles,
+ * measured from a common origin per round) at which the processes reach the collective.
+ * Host only, pure, deterministic.
+ *   EAGER_SOLO     (Section 4.1) the first process to arrive is the initiator.
+ *   EAGER_MAJORITY (Section 4.2) the initiator is a rank all processes derive from a
+ *                  shared seed: SplitMix64 output function of seed + (step+1)*gamma,
+ *                  reduced mod P.
+ * Active = the initiator and every process that arrived no later than the initiator
+ * plus window_ms (Section 7.1; the window models the activation reaching processes that
+ * arrive at a similar time, Section 4.2; use 0 for the paper's definition).  Ties count
+ * as on time; a tie for first place goes to the lowest rank.
+ * flags: EAGER_FLAG_STRICT_QUORUM (majority only) also waits for ceil(P/2) arrivals.
+ * Errors: EINVAL (NULL, P outside 1..64, unknown mode, NaN time, negative window).
+ */
+int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t seed,
+                             uint64_t step, double window_ms, uint32_t flags,
+                             eager_plan *out);
+
+/*
+ * One round of the partial allreduce over buckets [b0, b1) (Section 5; Algorithm 2
+ * line 6), optionally fused with the update rule (lines 7-8).
+ *   plan    host; produced by eager_plan_participation or built by the caller
+ *   grads   host array of P device pointers: G_p arena bases (fp32 or bf16 as created),
+ *           16-byte aligned, read only
+ *   resid   host array of P device pointers: R_p arena bases (fp32), 16-byte aligned.
+ *           Read where the process' send buffer is non-empty, written for passive
+ *           processes; content is meaningful only where the validity bit is set
+ *   recv    device, fp32 arena base or NULL: receive buffer, gets u = sum/P (Section
+ *           4.1.1: holds the value of the latest execution)
+ *   opt     host or NULL.  Non-NULL: w and v are updated in the same pass.  NULL:
+ *           only recv is produced (then recv must not be NULL)
+ * On success the validity of every bucket in the range becomes ~mask.
+ * The two entry points run the same kernels and differ in what they accept:
+ * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY.
+ * Errors: EINVAL (NULL, alignment, b0 >= b1, range), ESTATE (mode or P mismatch,
+ * initiator not in mask, nap != popcount(mask), mask beyond P bits, bucket already
+ * stepped with this plan->step), EDEVICE.  Non-finite gradients are not an error; they
+ * propagate through the arithmetic.
+ */
+int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                 const void *const *grads, float *const *resid,
+                                 float *recv, const eager_opt *opt, void *stream);
+int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                     const void *const *grads, float *const *resid,
+                                     float *recv, const eager_opt *opt, void *stream);
+
+/* The update rule alone (Algorithm 2, lines 7-8) on buckets [b0, b1): reads u from
+ * `update` (device fp32 arena, e.g. a receive buffer), updates opt->params/momentum.
+ * Errors: EINVAL, EDEVICE. */
+int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update,
+                   const eager_opt *opt, void *stream);
+
+/* Send-buffer validity of one bucket (bit p: R_p holds an undelivered gradient);
+ * together with w, v, R and the round index this is all the state a resume needs. */
+int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask);
+int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
+
+/*
+ * Launch shape of the round kernel, for measurement sweeps.  Unknown keys: EINVAL.
+ *   "block"      threads per workgroup: 64, 128, 256 or 512
+ *   "max_blocks" 0 = one workgroup per tile; otherwise a cap, workgroups then stride
+ *   "unroll"     16-byte vectors per thread and iteration: 1 or 2
+ *   "nontemporal" 1 = streaming cache hints on G and R, 0 = plain loads and stores
+ */
+int eager_set_launch(eager_ctx *ctx, const char *key, int value);
+
+/* Plain streaming kernels of known traffic, to calibrate bandwidth and the profiler's
+ * byte counters against the round kernel.  nbytes must be a multiple of 16, pointers
+ * 16-byte aligned device memory.  copy: dst <- src.  read: sums src into *sink. */
+int eager_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+int eager_calib_read(const void *src, int64_t nbytes, float *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EAGER_H */

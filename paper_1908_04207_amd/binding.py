@@ -1,0 +1,212 @@
+"""ctypes binding of libeager.so: argument marshalling only.
+
+Every step of a round runs in the library's HIP kernels; nothing here computes.  There
+is no fallback: if the shared library is missing the import of this module fails.
+PyTorch tensors are accepted as device buffers (their data_ptr is passed on) and the
+current torch stream is used unless a stream is given.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libeager.so")
+
+SOLO, MAJORITY = 0, 1
+F32, BF16 = 0, 1
+ORDER_FIXED, ORDER_FAST = 0, 1
+OK, EINVAL, ESHAPE, ESTATE, EDEVICE, ENOMEM = range(6)
+FLAG_STRICT_QUORUM = 1
+MAX_P = 64
+
+EXPORTS = (
+    "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
+    "eager_plan_participation", "eager_partial_allreduce_solo",
+    "eager_partial_allreduce_majority", "eager_sgd_step", "eager_get_valid",
+    "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
+)
+
+
+class EagerError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{text} (status {status})")
+        self.status = status
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("P", ctypes.c_int32), ("step", ctypes.c_uint64),
+                ("mask", ctypes.c_uint64), ("initiator", ctypes.c_int32),
+                ("nap", ctypes.c_int32)]
+
+    def __repr__(self):
+        return (f"Plan(mode={self.mode}, P={self.P}, step={self.step}, mask={self.mask:#x}, "
+                f"initiator={self.initiator}, nap={self.nap})")
+
+
+class Opt(ctypes.Structure):
+    _fields_ = [("params", ctypes.c_void_p), ("momentum", ctypes.c_void_p),
+                ("lr", ctypes.c_float), ("mu", ctypes.c_float)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_1908_04207_amd.build` "
+            "(hipcc, gfx950); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
+    lib.eager_create.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(i64),
+                                 ctypes.POINTER(i64), i32, i32]
+    lib.eager_destroy.argtypes = [vp]
+    lib.eager_last_error.argtypes = [vp]
+    lib.eager_last_error.restype = ctypes.c_char_p
+    lib.eager_status_string.argtypes = [i32]
+    lib.eager_status_string.restype = ctypes.c_char_p
+    lib.eager_plan_participation.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), u64, u64,
+                                             ctypes.c_double, ctypes.c_uint32,
+                                             ctypes.POINTER(Plan)]
+    for f in (lib.eager_partial_allreduce_solo, lib.eager_partial_allreduce_majority):
+        f.argtypes = [vp, ctypes.POINTER(Plan), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                      vp, ctypes.POINTER(Opt), vp]
+    lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
+    lib.eager_get_valid.argtypes = [vp, i32, ctypes.POINTER(u64)]
+    lib.eager_set_valid.argtypes = [vp, i32, u64]
+    lib.eager_set_launch.argtypes = [vp, ctypes.c_char_p, i32]
+    lib.eager_calib_copy.argtypes = [vp, vp, i64, vp]
+    lib.eager_calib_read.argtypes = [vp, i64, vp, vp]
+    return lib
+
+
+lib = _load()
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()            # torch tensor
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def status_string(status: int) -> str:
+    return lib.eager_status_string(status).decode()
+
+
+def eager_plan_participation(mode: int, arrival_ms: Sequence[float], seed: int, step: int,
+                             window_ms: float = 0.0, flags: int = 0) -> Plan:
+    P = len(arrival_ms)
+    arr = (ctypes.c_double * max(P, 1))(*arrival_ms)
+    plan = Plan()
+    st = lib.eager_plan_participation(mode, P, arr, seed & (2 ** 64 - 1), step, window_ms, flags,
+                                      ctypes.byref(plan))
+    if st != OK:
+        raise EagerError(st, f"eager_plan_participation: {status_string(st)}")
+    return plan
+
+
+def make_plan(mode: int, P: int, step: int, mask: int, initiator: Optional[int] = None) -> Plan:
+    """A plan the caller decides itself (tests, forced masks)."""
+    if initiator is None:
+        initiator = (mask & -mask).bit_length() - 1
+    return Plan(mode, P, step, mask, initiator, bin(mask).count("1"))
+
+
+class Context:
+    """Owns one eager_ctx.  Buffers are passed per call and stay owned by the caller."""
+
+    def __init__(self, P: int, bucket_offset: Sequence[int], bucket_numel: Sequence[int],
+                 grad_dtype: int = F32, order: int = ORDER_FIXED):
+        n = len(bucket_offset)
+        if len(bucket_numel) != n:
+            raise ValueError("bucket_offset and bucket_numel differ in length")
+        off = (ctypes.c_int64 * max(n, 1))(*bucket_offset)
+        num = (ctypes.c_int64 * max(n, 1))(*bucket_numel)
+        h = ctypes.c_void_p()
+        st = lib.eager_create(ctypes.byref(h), P, n, off, num, grad_dtype, order)
+        if st != OK:
+            raise EagerError(st, f"eager_create: {status_string(st)}")
+        self._h = h
+        self.P, self.n_buckets = P, n
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib.eager_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, st: int, what: str) -> None:
+        if st != OK:
+            raise EagerError(st, f"{what}: {status_string(st)}: "
+                                 f"{lib.eager_last_error(self._h).decode()}")
+
+    def _allreduce(self, fn, what, plan, grads, resid, recv, opt, b0, b1, stream):
+        b1 = self.n_buckets if b1 is None else b1
+        P = len(grads)
+        g = (ctypes.c_void_p * max(P, 1))(*[_ptr(x) for x in grads])
+        r = (ctypes.c_void_p * max(len(resid), 1))(*[_ptr(x) for x in resid])
+        o = None
+        if opt is not None:
+            params, momentum, lr, mu = opt
+            o = ctypes.byref(Opt(_ptr(params), _ptr(momentum), lr, mu))
+        if P != self.P or len(resid) != self.P:
+            raise EagerError(EINVAL, f"{what}: expected {self.P} gradient and send buffers")
+        self._check(fn(self._h, ctypes.byref(plan), b0, b1, g, r, _ptr(recv), o, _stream(stream)),
+                    what)
+
+    def eager_partial_allreduce_solo(self, plan: Plan, grads, resid, recv=None, opt=None,
+                                     b0: int = 0, b1: Optional[int] = None, stream=None):
+        self._allreduce(lib.eager_partial_allreduce_solo, "eager_partial_allreduce_solo", plan,
+                        grads, resid, recv, opt, b0, b1, stream)
+
+    def eager_partial_allreduce_majority(self, plan: Plan, grads, resid, recv=None, opt=None,
+                                         b0: int = 0, b1: Optional[int] = None, stream=None):
+        self._allreduce(lib.eager_partial_allreduce_majority, "eager_partial_allreduce_majority",
+                        plan, grads, resid, recv, opt, b0, b1, stream)
+
+    def eager_partial_allreduce(self, plan: Plan, *a, **kw):
+        """Dispatch on plan.mode to the entry point of that name."""
+        fn = (self.eager_partial_allreduce_solo if plan.mode == SOLO
+              else self.eager_partial_allreduce_majority)
+        fn(plan, *a, **kw)
+
+    def eager_sgd_step(self, update, opt, b0: int = 0, b1: Optional[int] = None, stream=None):
+        b1 = self.n_buckets if b1 is None else b1
+        params, momentum, lr, mu = opt
+        o = Opt(_ptr(params), _ptr(momentum), lr, mu)
+        self._check(lib.eager_sgd_step(self._h, b0, b1, _ptr(update), ctypes.byref(o),
+                                       _stream(stream)), "eager_sgd_step")
+
+    def eager_get_valid(self, bucket: int) -> int:
+        v = ctypes.c_uint64()
+        self._check(lib.eager_get_valid(self._h, bucket, ctypes.byref(v)), "eager_get_valid")
+        return v.value
+
+    def eager_set_valid(self, bucket: int, valid_mask: int) -> None:
+        self._check(lib.eager_set_valid(self._h, bucket, valid_mask), "eager_set_valid")
+
+    def eager_set_launch(self, key: str, value: int) -> None:
+        self._check(lib.eager_set_launch(self._h, key.encode(), value), "eager_set_launch")
+
+
+def eager_calib_copy(dst, src, nbytes: int, stream=None) -> None:
+    st = lib.eager_calib_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+    if st != OK:
+        raise EagerError(st, f"eager_calib_copy: {status_string(st)}")
+
+
+def eager_calib_read(src, nbytes: int, sink, stream=None) -> None:
+    st = lib.eager_calib_read(_ptr(src), nbytes, _ptr(sink), _stream(stream))
+    if st != OK:
+        raise EagerError(st, f"eager_calib_read: {status_string(st)}")

@@ -1,0 +1,350 @@
+// Host side of the C ABI: context state (bucket table, send-buffer validity per bucket),
+// argument checking, the participation plan, and the split of a bucket range into runs
+// that one kernel launch each can cover.  All arithmetic of a round runs in the kernels.
+#include "../../include/eager.h"
+#include "eager_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+struct eager_ctx {
+    int P = 0;
+    int n_buckets = 0;
+    bool bf16 = false;
+    bool fast = false;
+    std::vector<int64_t> offset, numel;
+    std::vector<uint64_t> valid;       // per bucket: bit p = R_p holds an undelivered gradient
+    std::vector<uint64_t> last_step;   // per bucket: round it was last stepped with
+    std::vector<uint8_t> stepped;      // per bucket: last_step is meaningful
+    eager::Launch launch;
+    std::string err;
+};
+
+namespace {
+
+int fail(eager_ctx *ctx, int status, const char *fmt, ...)
+{
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return status;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int popcount64(uint64_t x) { return __builtin_popcountll(x); }
+
+uint64_t low_bits(int P) { return P >= 64 ? ~0ull : ((1ull << P) - 1ull); }
+
+// SplitMix64 output function on seed + (step+1)*gamma: the shared-seed draw of the
+// designated initiator (paper Section 4.2).
+uint64_t initiator_hash(uint64_t seed, uint64_t step)
+{
+    uint64_t z = seed + (step + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+int check_range(eager_ctx *ctx, int b0, int b1)
+{
+    if (b0 < 0 || b1 > ctx->n_buckets || b0 >= b1)
+        return fail(ctx, EAGER_EINVAL, "bucket range [%d, %d) is empty or outside 0..%d", b0, b1,
+                    ctx->n_buckets);
+    return EAGER_OK;
+}
+
+int check_opt(eager_ctx *ctx, const eager_opt *opt)
+{
+    if (!opt->params || !opt->momentum)
+        return fail(ctx, EAGER_EINVAL, "opt->params and opt->momentum must not be NULL");
+    if (!aligned16(opt->params) || !aligned16(opt->momentum))
+        return fail(ctx, EAGER_EINVAL, "opt->params / opt->momentum must be 16-byte aligned");
+    return EAGER_OK;
+}
+
+int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int b0, int b1,
+                      const void *const *grads, float *const *resid, float *recv,
+                      const eager_opt *opt, void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!plan || !grads || !resid) return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    if (!opt && !recv)
+        return fail(ctx, EAGER_EINVAL, "nothing to produce: recv and opt are both NULL");
+    if (opt) {
+        if (int st = check_opt(ctx, opt)) return st;
+    }
+    if (recv && !aligned16(recv)) return fail(ctx, EAGER_EINVAL, "recv must be 16-byte aligned");
+    const int P = ctx->P;
+    if (plan->mode != want_mode)
+        return fail(ctx, EAGER_ESTATE, "plan->mode %d does not match this entry point (%d)",
+                    plan->mode, want_mode);
+    if (plan->P != P) return fail(ctx, EAGER_ESTATE, "plan->P %d != context P %d", plan->P, P);
+    if (plan->mask & ~low_bits(P)) return fail(ctx, EAGER_ESTATE, "plan->mask has bits beyond P");
+    if (plan->nap != popcount64(plan->mask) || plan->nap < 1)
+        return fail(ctx, EAGER_ESTATE, "plan->nap %d is not popcount(mask) >= 1", plan->nap);
+    if (plan->initiator < 0 || plan->initiator >= P || !((plan->mask >> plan->initiator) & 1ull))
+        return fail(ctx, EAGER_ESTATE, "initiator %d is not in the mask", plan->initiator);
+    for (int p = 0; p < P; ++p) {
+        if (!grads[p] || !resid[p]) return fail(ctx, EAGER_EINVAL, "grads[%d] or resid[%d] is NULL", p, p);
+        if (!aligned16(grads[p]) || !aligned16(resid[p]))
+            return fail(ctx, EAGER_EINVAL, "grads[%d] / resid[%d] must be 16-byte aligned", p, p);
+    }
+    for (int b = b0; b < b1; ++b)
+        if (ctx->stepped[b] && ctx->last_step[b] == plan->step)
+            return fail(ctx, EAGER_ESTATE, "bucket %d was already stepped with round %llu", b,
+                        static_cast<unsigned long long>(plan->step));
+
+    eager::RoundArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (int p = 0; p < P; ++p) {
+        a.g[p] = grads[p];
+        a.r[p] = resid[p];
+    }
+    a.active = plan->mask;
+    a.passive = ~plan->mask & low_bits(P);
+    a.w = opt ? opt->params : nullptr;
+    a.v = opt ? opt->momentum : nullptr;
+    a.recv = recv;
+    a.P = P;
+    a.inv_P = 1.0f / static_cast<float>(P);
+    a.neg_lr = opt ? -opt->lr : 0.0f;
+    a.mu = opt ? opt->mu : 0.0f;
+
+    // Consecutive buckets whose send buffers are in the same state form one run = one
+    // launch over a contiguous element range (after a whole-model round every bucket is
+    // in the same state, so a round is normally a single launch however small the
+    // buckets are).
+    int b = b0;
+    while (b < b1) {
+        int e = b + 1;
+        while (e < b1 && ctx->valid[e] == ctx->valid[b]) ++e;
+        a.valid = ctx->valid[b];
+        a.e0 = ctx->offset[b];
+        a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
+        a.dummy = static_cast<const char *>(grads[0]) + a.e0 * (ctx->bf16 ? 2 : 4);
+        hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
+                                            static_cast<hipStream_t>(stream));
+        if (he != hipSuccess)
+            return fail(ctx, EAGER_EDEVICE, "round kernel launch failed: %s", hipGetErrorString(he));
+        for (int k = b; k < e; ++k) {
+            ctx->valid[k] = ~plan->mask & low_bits(P);
+            ctx->last_step[k] = plan->step;
+            ctx->stepped[k] = 1;
+        }
+        b = e;
+    }
+    ctx->err.clear();
+    return EAGER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int eager_create(eager_ctx **out, int P, int n_buckets, const int64_t *bucket_offset,
+                 const int64_t *bucket_numel, int grad_dtype, int order)
+{
+    if (!out) return EAGER_EINVAL;
+    *out = nullptr;
+    if (!bucket_offset || !bucket_numel) return EAGER_EINVAL;
+    if (P < 1 || P > EAGER_MAX_P || n_buckets < 1) return EAGER_EINVAL;
+    if (grad_dtype != EAGER_F32 && grad_dtype != EAGER_BF16) return EAGER_EINVAL;
+    if (order != EAGER_ORDER_FIXED && order != EAGER_ORDER_FAST) return EAGER_EINVAL;
+    const int64_t align = grad_dtype == EAGER_BF16 ? 8 : 4;
+    int64_t end = 0;
+    for (int b = 0; b < n_buckets; ++b) {
+        if (bucket_numel[b] < 0 || bucket_offset[b] < end || bucket_offset[b] % align != 0)
+            return EAGER_ESHAPE;
+        if (bucket_numel[b] > INT64_MAX / 8 - bucket_offset[b]) return EAGER_ESHAPE;
+        end = bucket_offset[b] + bucket_numel[b];
+    }
+    eager_ctx *c = new (std::nothrow) eager_ctx;
+    if (!c) return EAGER_ENOMEM;
+    try {
+        c->P = P;
+        c->n_buckets = n_buckets;
+        c->bf16 = grad_dtype == EAGER_BF16;
+        c->fast = order == EAGER_ORDER_FAST;
+        c->offset.assign(bucket_offset, bucket_offset + n_buckets);
+        c->numel.assign(bucket_numel, bucket_numel + n_buckets);
+        c->valid.assign(n_buckets, 0);
+        c->last_step.assign(n_buckets, 0);
+        c->stepped.assign(n_buckets, 0);
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return EAGER_ENOMEM;
+    }
+    *out = c;
+    return EAGER_OK;
+}
+
+int eager_destroy(eager_ctx *ctx)
+{
+    delete ctx;
+    return EAGER_OK;
+}
+
+const char *eager_last_error(const eager_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+const char *eager_status_string(int status)
+{
+    switch (status) {
+    case EAGER_OK: return "EAGER_OK";
+    case EAGER_EINVAL: return "EAGER_EINVAL";
+    case EAGER_ESHAPE: return "EAGER_ESHAPE";
+    case EAGER_ESTATE: return "EAGER_ESTATE";
+    case EAGER_EDEVICE: return "EAGER_EDEVICE";
+    case EAGER_ENOMEM: return "EAGER_ENOMEM";
+    default: return "EAGER_<unknown>";
+    }
+}
+
+int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t seed,
+                             uint64_t step, double window_ms, uint32_t flags, eager_plan *out)
+{
+    if (!arrival_ms || !out) return EAGER_EINVAL;
+    if (P < 1 || P > EAGER_MAX_P) return EAGER_EINVAL;
+    if (mode != EAGER_SOLO && mode != EAGER_MAJORITY) return EAGER_EINVAL;
+    if (!(window_ms >= 0.0)) return EAGER_EINVAL;
+    for (int p = 0; p < P; ++p)
+        if (std::isnan(arrival_ms[p])) return EAGER_EINVAL;
+
+    int init = 0;
+    if (mode == EAGER_SOLO) {
+        for (int p = 1; p < P; ++p)
+            if (arrival_ms[p] < arrival_ms[init]) init = p;   // strict: lowest rank wins a tie
+    } else {
+        init = static_cast<int>(initiator_hash(seed, step) % static_cast<uint64_t>(P));
+    }
+    double threshold = arrival_ms[init] + window_ms;
+    if (mode == EAGER_MAJORITY && (flags & EAGER_FLAG_STRICT_QUORUM)) {
+        // the time by which ceil(P/2) processes have arrived
+        const int need = (P + 1) / 2;
+        double sorted[EAGER_MAX_P];
+        for (int p = 0; p < P; ++p) sorted[p] = arrival_ms[p];
+        for (int i = 1; i < P; ++i) {
+            const double x = sorted[i];
+            int j = i - 1;
+            while (j >= 0 && sorted[j] > x) { sorted[j + 1] = sorted[j]; --j; }
+            sorted[j + 1] = x;
+        }
+        if (sorted[need - 1] > threshold) threshold = sorted[need - 1];
+    }
+    uint64_t mask = 0;
+    for (int p = 0; p < P; ++p)
+        if (arrival_ms[p] <= threshold) mask |= 1ull << p;
+    out->mode = mode;
+    out->P = P;
+    out->step = step;
+    out->mask = mask;
+    out->initiator = init;
+    out->nap = popcount64(mask);
+    return EAGER_OK;
+}
+
+int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                 const void *const *grads, float *const *resid, float *recv,
+                                 const eager_opt *opt, void *stream)
+{
+    return partial_allreduce(ctx, EAGER_SOLO, plan, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                     const void *const *grads, float *const *resid, float *recv,
+                                     const eager_opt *opt, void *stream)
+{
+    return partial_allreduce(ctx, EAGER_MAJORITY, plan, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+                   void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!update || !opt) return fail(ctx, EAGER_EINVAL, "update and opt must not be NULL");
+    if (!aligned16(update)) return fail(ctx, EAGER_EINVAL, "update must be 16-byte aligned");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    if (int st = check_opt(ctx, opt)) return st;
+    eager::SgdArgs a;
+    a.u = update;
+    a.w = opt->params;
+    a.v = opt->momentum;
+    a.e0 = ctx->offset[b0];
+    a.n = ctx->offset[b1 - 1] + ctx->numel[b1 - 1] - ctx->offset[b0];
+    a.neg_lr = -opt->lr;
+    a.mu = opt->mu;
+    hipError_t he = eager::launch_sgd(a, ctx->fast, ctx->launch, static_cast<hipStream_t>(stream));
+    if (he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "sgd kernel launch failed: %s", hipGetErrorString(he));
+    ctx->err.clear();
+    return EAGER_OK;
+}
+
+int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask)
+{
+    if (!ctx || !valid_mask || bucket < 0 || bucket >= ctx->n_buckets) return EAGER_EINVAL;
+    *valid_mask = ctx->valid[bucket];
+    return EAGER_OK;
+}
+
+int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (bucket < 0 || bucket >= ctx->n_buckets) return fail(ctx, EAGER_EINVAL, "bucket %d out of range", bucket);
+    if (valid_mask & ~low_bits(ctx->P)) return fail(ctx, EAGER_EINVAL, "validity mask has bits beyond P");
+    ctx->valid[bucket] = valid_mask;
+    ctx->stepped[bucket] = 0;
+    return EAGER_OK;
+}
+
+int eager_set_launch(eager_ctx *ctx, const char *key, int value)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!key) return fail(ctx, EAGER_EINVAL, "key is NULL");
+    if (!std::strcmp(key, "block")) {
+        if (value != 64 && value != 128 && value != 256 && value != 512)
+            return fail(ctx, EAGER_EINVAL, "block must be 64, 128, 256 or 512");
+        ctx->launch.block = value;
+    } else if (!std::strcmp(key, "max_blocks")) {
+        if (value < 0) return fail(ctx, EAGER_EINVAL, "max_blocks must be >= 0");
+        ctx->launch.max_blocks = value;
+    } else if (!std::strcmp(key, "unroll")) {
+        if (value != 1 && value != 2)
+            return fail(ctx, EAGER_EINVAL, "unroll must be 1 or 2");
+        ctx->launch.unroll = value;
+    } else if (!std::strcmp(key, "nontemporal")) {
+        if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "nontemporal must be 0 or 1");
+        ctx->launch.nontemporal = value;
+    } else {
+        return fail(ctx, EAGER_EINVAL, "unknown launch key '%s'", key);
+    }
+    return EAGER_OK;
+}
+
+int eager_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes < 0 || nbytes % 16 || !aligned16(dst) || !aligned16(src))
+        return EAGER_EINVAL;
+    return eager::launch_copy(dst, src, nbytes, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? EAGER_OK : EAGER_EDEVICE;
+}
+
+int eager_calib_read(const void *src, int64_t nbytes, float *sink, void *stream)
+{
+    if (!src || !sink || nbytes < 0 || nbytes % 16 || !aligned16(src)) return EAGER_EINVAL;
+    return eager::launch_read(src, nbytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? EAGER_OK : EAGER_EDEVICE;
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal interface between the host side of the library (argument checking, context
+// state, run building) and the gfx950 kernels.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eager {
+
+constexpr int kMaxP = 64;
+
+// Everything one launch of the round kernel needs, passed by value in the kernel
+// argument segment: the P gradient and send-buffer bases stay in scalar registers and
+// every per-rank decision is uniform across the grid.
+struct RoundArgs {
+    const void *g[kMaxP];        // G_p arena bases (fp32 or bf16)
+    float *r[kMaxP];             // R_p arena bases (fp32)
+    unsigned long long active;   // bit p: process p is on time in this round
+    unsigned long long valid;    // bit p: R_p holds an undelivered gradient
+    unsigned long long passive;  // bit p: process p is late (p < P and not active)
+    const void *dummy;           // 16 readable bytes: stands in for streams not to be read
+    float *w;                    // parameters (NULL: no update rule)
+    float *v;                    // momentum
+    float *recv;                 // receive buffer (NULL: not wanted)
+    long long e0;                // first element of the run (arena index)
+    long long n;                 // elements in the run
+    int P;
+    float inv_P;                 // 1.0f / (float)P
+    float neg_lr;                // -lr
+    float mu;
+};
+
+struct SgdArgs {
+    const float *u;
+    float *w;
+    float *v;
+    long long e0;
+    long long n;
+    float neg_lr;
+    float mu;
+};
+
+struct Launch {
+    int block = 256;       // threads per workgroup
+    int max_blocks = 0;    // 0: one workgroup per tile
+    int unroll = 1;        // 16-byte vectors per thread and iteration
+    int nontemporal = 1;   // streaming hints on G and R
+};
+
+hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
+                        hipStream_t stream);
+hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
+hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
+hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);
+
+}  // namespace eager

@@ -1,0 +1,123 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, plans participation exactly like the oracle, and rejects bad
+arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import eager_oracle as eo
+from paper_1908_04207_amd import binding as eb
+from workloads import shapes, times
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "eager.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(eager_[a-z_]+)\s*\(", header))
+    assert declared == set(eb.EXPORTS)
+    lib = ctypes.CDLL(eb.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_plan_matches_oracle_on_all_configs():
+    for k in range(1, 6):
+        cfg = shapes.config(k)
+        lm = eb.SOLO if cfg.mode == "solo" else eb.MAJORITY
+        om = eo.SOLO if cfg.mode == "solo" else eo.MAJORITY
+        for step in range(cfg.steps):
+            t = times.compute_times(cfg.times, cfg.P, cfg.seed, step)
+            a = eb.eager_plan_participation(lm, t, cfg.seed, step)
+            b = eo.plan_participation(om, cfg.P, t, cfg.seed, step)
+            assert (a.mode, a.P, a.step, a.mask, a.initiator, a.nap) == \
+                   (lm, cfg.P, step, b.mask, b.initiator, b.nap)
+
+
+def test_plan_matches_oracle_random_with_ties_window_and_strict_quorum():
+    rng = np.random.default_rng(0)
+    for it in range(2000):
+        P = int(rng.integers(1, 65))
+        t = rng.integers(0, 6, P).astype(float).tolist() if it % 2 else rng.random(P).tolist()
+        seed = int(rng.integers(0, 2 ** 63))
+        window = float(rng.choice([0.0, 0.5, 2.0]))
+        for lm, om in ((eb.SOLO, eo.SOLO), (eb.MAJORITY, eo.MAJORITY)):
+            for flags in (0, eb.FLAG_STRICT_QUORUM):
+                a = eb.eager_plan_participation(lm, t, seed, it, window, flags)
+                b = eo.plan_participation(om, P, t, seed, it, window, flags)
+                assert (a.mask, a.initiator, a.nap) == (b.mask, b.initiator, b.nap)
+
+
+def test_plan_rejects_bad_arguments():
+    for bad in (lambda: eb.eager_plan_participation(7, [1.0], 0, 0),
+                lambda: eb.eager_plan_participation(eb.SOLO, [], 0, 0),
+                lambda: eb.eager_plan_participation(eb.SOLO, [1.0] * 65, 0, 0),
+                lambda: eb.eager_plan_participation(eb.SOLO, [float("nan")], 0, 0),
+                lambda: eb.eager_plan_participation(eb.SOLO, [1.0], 0, 0, window_ms=-1.0)):
+        with pytest.raises(eb.EagerError) as e:
+            bad()
+        assert e.value.status == eb.EINVAL
+
+
+def test_create_rejects_bad_bucket_tables():
+    for P, off, num, dt, status in (
+            (0, [0], [4], eb.F32, eb.EINVAL), (65, [0], [4], eb.F32, eb.EINVAL),
+            (2, [], [], eb.F32, eb.EINVAL), (2, [0], [4], 9, eb.EINVAL),
+            (2, [0, 2], [2, 4], eb.F32, eb.ESHAPE),      # start not 16-byte aligned
+            (2, [0, 4], [2, 4], eb.BF16, eb.ESHAPE),     # bf16 needs multiples of 8
+            (2, [0, 4], [8, 4], eb.F32, eb.ESHAPE),      # overlap
+            (2, [0], [-1], eb.F32, eb.ESHAPE)):
+        with pytest.raises(eb.EagerError) as e:
+            eb.Context(P, off, num, dt)
+        assert e.value.status == status
+    c = eb.Context(64, [0, 8, 16], [5, 0, 3], eb.BF16, eb.ORDER_FAST)
+    assert c.eager_get_valid(2) == 0
+    c.close()
+
+
+def test_allreduce_validation_happens_before_any_launch():
+    """Every case below must be refused on the host; fake device addresses are never
+    dereferenced, so this runs without a GPU."""
+    P = 4
+    c = eb.Context(P, [0, 8], [8, 8])
+    fake = [0x10000 + 0x1000 * p for p in range(P)]
+    opt = (0x90000, 0xA0000, 0.1, 0.9)
+    ok = eb.make_plan(eb.SOLO, P, 0, 0b0011)
+
+    def expect(status, plan, **kw):
+        args = dict(grads=fake, resid=fake, recv=None, opt=opt, b0=0, b1=2, stream=0)
+        args.update(kw)
+        with pytest.raises(eb.EagerError) as e:
+            c.eager_partial_allreduce_solo(plan, args["grads"], args["resid"], args["recv"],
+                                           args["opt"], args["b0"], args["b1"], args["stream"])
+        assert e.value.status == status, str(e.value)
+
+    expect(eb.ESTATE, eb.make_plan(eb.MAJORITY, P, 0, 0b0011))          # wrong entry point
+    expect(eb.ESTATE, eb.make_plan(eb.SOLO, 5, 0, 0b0011))              # P mismatch
+    expect(eb.ESTATE, eb.make_plan(eb.SOLO, P, 0, 0b10011))             # mask beyond P
+    expect(eb.ESTATE, eb.make_plan(eb.SOLO, P, 0, 0b0011, initiator=3))  # initiator not active
+    expect(eb.ESTATE, eb.Plan(eb.SOLO, P, 0, 0b0011, 0, 3))             # nap wrong
+    expect(eb.ESTATE, eb.Plan(eb.SOLO, P, 0, 0, 0, 0))                  # nobody active
+    expect(eb.EINVAL, ok, b0=1, b1=1)
+    expect(eb.EINVAL, ok, b1=3)
+    expect(eb.EINVAL, ok, opt=None)                                     # nothing to produce
+    expect(eb.EINVAL, ok, grads=[0x10004] + fake[1:])                   # misaligned
+    expect(eb.EINVAL, ok, resid=[0] + fake[1:])                         # NULL
+    expect(eb.EINVAL, ok, opt=(0x90008, 0xA0000, 0.1, 0.9))
+    expect(eb.EINVAL, ok, recv=0x90004)
+    with pytest.raises(eb.EagerError) as e:
+        c.eager_sgd_step(0, opt, stream=0)
+    assert e.value.status == eb.EINVAL
+    with pytest.raises(eb.EagerError):
+        c.eager_set_launch("block", 100)
+    with pytest.raises(eb.EagerError):
+        c.eager_set_launch("nonsense", 1)
+    with pytest.raises(eb.EagerError):
+        c.eager_set_valid(0, 1 << P)
+    c.eager_set_valid(1, 0b1010)
+    assert c.eager_get_valid(1) == 0b1010 and c.eager_get_valid(0) == 0
+    c.close()
