@@ -152,14 +152,16 @@ def cpu_baseline(wl: Workload, budget_s: float = 20.0) -> dict:
     cfg = wl.cfg
     bt = cfg.buckets
     cores = len(os.sched_getaffinity(0))
-    # leading buckets up to ~4M elements per process keep the sample to seconds
+    # whole buckets from the front of the arena, at most 2^25 elements per process (the
+    # whole model where it is smaller); the round loop below stops at the time budget
+    cap = 1 << 25
     nb, tot = 0, 0
-    while nb < bt.n_buckets and (nb == 0 or tot + bt.numel[nb] <= (1 << 22)):
+    while nb < bt.n_buckets and (nb == 0 or tot + bt.numel[nb] <= cap):
         tot += bt.numel[nb]
         nb += 1
     hi = bt.offset[nb - 1] + bt.numel[nb - 1]
-    if bt.numel[0] > (1 << 22):              # a single huge first bucket: take a slice of it
-        hi, tot = 1 << 22, 1 << 22
+    if bt.numel[0] > cap:                    # a single huge first bucket: take a slice of it
+        hi, tot = cap, cap
         offs, nums = [0], [hi]
     else:
         offs, nums = list(bt.offset[:nb]), list(bt.numel[:nb])
