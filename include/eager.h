@@ -158,10 +158,15 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
 
 /*
  * Launch shape of the round kernel, for measurement sweeps.  Unknown keys: EINVAL.
- *   "block"      threads per workgroup: 64, 128, 256 or 512
+ *   "block"      threads per workgroup: 64 (default), 128 or 256
  *   "max_blocks" 0 = one workgroup per tile; otherwise a cap, workgroups then stride
  *   "unroll"     16-byte vectors per thread and iteration: 1 or 2
  *   "nontemporal" 1 = streaming cache hints on G and R, 0 = plain loads and stores
+ *   "chunk"      ranks whose loads are in flight together: 0 (chosen from P), 4, 8, 16, 32
+ *                (32 only with fp32 gradients and unroll 1, 16 with bf16 gradients only
+ *                with unroll 1; otherwise the launch fails with EDEVICE)
+ *   "blocks_per_cu" 0 = chosen from P and block (default); -1 = no cap; 1..32 = at most
+ *                that many workgroups resident per CU
  */
 int eager_set_launch(eager_ctx *ctx, const char *key, int value);
 

@@ -140,7 +140,7 @@ class Context:
         self.P, self.n_buckets = P, n
 
     def close(self) -> None:
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and lib is not None:   # lib is None at interpreter exit
             lib.eager_destroy(self._h)
             self._h = None
 

@@ -313,8 +313,8 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
     if (!ctx) return EAGER_EINVAL;
     if (!key) return fail(ctx, EAGER_EINVAL, "key is NULL");
     if (!std::strcmp(key, "block")) {
-        if (value != 64 && value != 128 && value != 256 && value != 512)
-            return fail(ctx, EAGER_EINVAL, "block must be 64, 128, 256 or 512");
+        if (value != 64 && value != 128 && value != 256)
+            return fail(ctx, EAGER_EINVAL, "block must be 64, 128 or 256");
         ctx->launch.block = value;
     } else if (!std::strcmp(key, "max_blocks")) {
         if (value < 0) return fail(ctx, EAGER_EINVAL, "max_blocks must be >= 0");
@@ -326,6 +326,13 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
     } else if (!std::strcmp(key, "nontemporal")) {
         if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "nontemporal must be 0 or 1");
         ctx->launch.nontemporal = value;
+    } else if (!std::strcmp(key, "chunk")) {
+        if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32)
+            return fail(ctx, EAGER_EINVAL, "chunk must be 0, 4, 8, 16 or 32");
+        ctx->launch.chunk = value;
+    } else if (!std::strcmp(key, "blocks_per_cu")) {
+        if (value < -1 || value > 32) return fail(ctx, EAGER_EINVAL, "blocks_per_cu must be -1..32");
+        ctx->launch.blocks_per_cu = value;
     } else {
         return fail(ctx, EAGER_EINVAL, "unknown launch key '%s'", key);
     }

@@ -41,10 +41,12 @@ struct SgdArgs {
 };
 
 struct Launch {
-    int block = 256;       // threads per workgroup
+    int block = 64;        // threads per workgroup
     int max_blocks = 0;    // 0: one workgroup per tile
     int unroll = 1;        // 16-byte vectors per thread and iteration
     int nontemporal = 1;   // streaming hints on G and R
+    int chunk = 0;         // ranks whose loads are in flight together; 0: chosen from P
+    int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
 };
 
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,

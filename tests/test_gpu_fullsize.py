@@ -1,0 +1,106 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The whole arenas live only on the GPU (up to 162 GB); gradients are produced there by the
+seeded counter-based generator.  The oracle recomputes a sample of elements one by one:
+the path is elementwise, so the oracle run on the gathered inputs of the sampled indices
+gives the exact expected values for those indices.  The sample holds every bucket's first
+and last elements, positions around workgroup-tile boundaries, the ragged tail of the
+arena and random positions.  Fixed-order mode: bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from harness import as_oracle_grad, bits, normwise, plan_for
+from oracle import eager_oracle as eo
+from workloads import grads as wg
+from workloads import shapes
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1908_04207_amd import binding
+    return binding
+
+
+def sample_indices(cfg, n_random=30000, seed=0):
+    bt = cfg.buckets
+    rng = np.random.default_rng(seed)
+    picks = []
+    for off, n in zip(bt.offset, bt.numel):
+        if n == 0:
+            continue
+        edge = np.concatenate([np.arange(min(n, 9)), n - 1 - np.arange(min(n, 9))])
+        picks.append(off + edge)
+    total_end = bt.offset[-1] + bt.numel[-1]
+    # around multiples of the tile sizes a launch may use (64..256 threads x 4 or 8 elements)
+    for tile in (256, 512, 1024, 2048, 4096):
+        ks = rng.integers(1, max(2, total_end // tile), 200)
+        for d in (-1, 0, 1):
+            picks.append(ks * tile + d)
+    picks.append(rng.integers(0, total_end, n_random))
+    idx = np.unique(np.concatenate(picks))
+    idx = idx[(idx >= 0) & (idx < total_end)]
+    # keep only positions inside buckets (padding carries no data)
+    starts = np.asarray(bt.offset)
+    b = np.searchsorted(starts, idx, side="right") - 1
+    inside = idx < starts[b] + np.asarray(bt.numel)[b]
+    return idx[inside].astype(np.int64)
+
+
+@pytest.mark.parametrize("k,steps,order", [(2, 8, 0), (2, 4, 1), (3, 5, 0), (4, 3, 0), (5, 3, 0),
+                                           (5, 2, 1)])
+def test_full_size_sampled(eb, k, steps, order):
+    cfg = shapes.config(k)
+    bt = cfg.buckets
+    dev = torch.device("cuda:0")
+    gdt = torch.bfloat16 if cfg.grad_dtype == "bf16" else torch.float32
+    n = bt.arena_numel
+    S = sample_indices(cfg)
+    S_t = torch.from_numpy(S)
+    S_dev = S_t.to(dev)
+
+    ctx = eb.Context(cfg.P, bt.offset, bt.numel, eb.BF16 if cfg.grad_dtype == "bf16" else eb.F32,
+                     order)
+    G = [torch.empty(n, dtype=gdt, device=dev) for _ in range(cfg.P)]
+    R = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(cfg.P)]
+    w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
+    v = torch.zeros(n, device=dev)
+
+    w0 = wg.values_at(S_t, cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma).numpy()
+    oracle = eo.OracleState(cfg.P, [0], [len(S)], len(S), w0, cfg.lr, cfg.mu)
+
+    for t in range(steps):
+        print(f"{cfg.name} order={order} step {t}", flush=True)
+        plan = plan_for(eb, cfg, t)
+        for p in range(cfg.P):
+            wg.fill(G[p], cfg.seed, t, p, cfg.grad_sigma)
+        ctx.eager_partial_allreduce(plan, G, R, opt=(w, v, cfg.lr, cfg.mu))
+        Gs = [as_oracle_grad(wg.grad_at(S_t, cfg.seed, t, p, cfg.grad_sigma, gdt))
+              for p in range(cfg.P)]
+        # the generator gives the same bits on both devices
+        assert np.array_equal(as_oracle_grad(G[t % cfg.P][S_dev]), Gs[t % cfg.P])
+        oracle.round(plan.mask, Gs)
+        torch.cuda.synchronize()
+        valid = ctx.eager_get_valid(0)
+        assert all(ctx.eager_get_valid(b) == valid for b in range(bt.n_buckets))
+        assert valid == oracle.valid[0]
+        got = {"w": w[S_dev].cpu().numpy(), "v": v[S_dev].cpu().numpy()}
+        want = {"w": oracle.w, "v": oracle.v}
+        for p in range(cfg.P):
+            if (valid >> p) & 1:
+                got[f"R{p}"] = R[p][S_dev].cpu().numpy()
+                want[f"R{p}"] = oracle.R[p]
+        for name in got:
+            if order == eb.ORDER_FIXED:
+                assert np.array_equal(bits(got[name]), bits(want[name])), \
+                    f"{cfg.name} step {t}: {name} differs at " \
+                    f"{int(np.sum(bits(got[name]) != bits(want[name])))} of {len(S)} samples"
+            else:
+                tol = 1e-2 if cfg.grad_dtype == "bf16" else 1e-6
+                assert normwise(got[name], want[name]) <= tol, (cfg.name, t, name)
+    ctx.close()
