@@ -162,6 +162,8 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
  *   "max_blocks" 0 = one workgroup per tile; otherwise a cap, workgroups then stride
  *   "unroll"     16-byte vectors per thread and iteration: 1 or 2
  *   "nontemporal" 1 = streaming cache hints on G and R, 0 = plain loads and stores
+ *   "split"      0 = chosen per round (default); 1 = one fused kernel; 2 = reduction + update
+ *                kernel followed by a copy kernel for the send buffers of late processes
  *   "chunk"      ranks whose loads are in flight together: 0 (chosen from P), 4, 8, 16, 32
  *                (32 only with fp32 gradients and unroll 1, 16 with bf16 gradients only
  *                with unroll 1; otherwise the launch fails with EDEVICE)

@@ -56,6 +56,17 @@ uint64_t initiator_hash(uint64_t seed, uint64_t step)
     return z ^ (z >> 31);
 }
 
+// Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
+// the reduction instead of inside it.
+bool use_split(const eager::Launch &l, int P, int n_late)
+{
+    if (l.split == 1) return false;
+    if (l.split == 2) return true;
+    (void)P;
+    (void)n_late;
+    return false;
+}
+
 int check_range(eager_ctx *ctx, int b0, int b1)
 {
     if (b0 < 0 || b1 > ctx->n_buckets || b0 >= b1)
@@ -113,7 +124,6 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.r[p] = resid[p];
     }
     a.active = plan->mask;
-    a.passive = ~plan->mask & low_bits(P);
     a.w = opt ? opt->params : nullptr;
     a.v = opt ? opt->momentum : nullptr;
     a.recv = recv;
@@ -134,10 +144,31 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.e0 = ctx->offset[b];
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
         a.dummy = static_cast<const char *>(grads[0]) + a.e0 * (ctx->bf16 ? 2 : 4);
+        const uint64_t late = ~plan->mask & low_bits(P);
+        const bool split = late != 0 && use_split(ctx->launch, P, popcount64(late));
+        a.gload = split ? plan->mask : low_bits(P);
+        a.store = split ? 0 : late;
         hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
                                             static_cast<hipStream_t>(stream));
         if (he != hipSuccess)
             return fail(ctx, EAGER_EDEVICE, "round kernel launch failed: %s", hipGetErrorString(he));
+        if (split) {
+            // same stream: the reduction has read every pending R_p before it is overwritten
+            eager::CarryArgs c;
+            std::memset(&c, 0, sizeof c);
+            for (int p = 0; p < P; ++p)
+                if ((late >> p) & 1ull) {
+                    c.src[c.count] = grads[p];
+                    c.dst[c.count] = resid[p];
+                    ++c.count;
+                }
+            c.e0 = a.e0;
+            c.n = a.n;
+            he = eager::launch_carry(c, ctx->bf16, static_cast<hipStream_t>(stream));
+            if (he != hipSuccess)
+                return fail(ctx, EAGER_EDEVICE, "carry kernel launch failed: %s",
+                            hipGetErrorString(he));
+        }
         for (int k = b; k < e; ++k) {
             ctx->valid[k] = ~plan->mask & low_bits(P);
             ctx->last_step[k] = plan->step;
@@ -326,6 +357,9 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
     } else if (!std::strcmp(key, "nontemporal")) {
         if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "nontemporal must be 0 or 1");
         ctx->launch.nontemporal = value;
+    } else if (!std::strcmp(key, "split")) {
+        if (value < 0 || value > 2) return fail(ctx, EAGER_EINVAL, "split must be 0, 1 or 2");
+        ctx->launch.split = value;
     } else if (!std::strcmp(key, "chunk")) {
         if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32)
             return fail(ctx, EAGER_EINVAL, "chunk must be 0, 4, 8, 16 or 32");

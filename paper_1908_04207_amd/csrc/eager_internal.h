@@ -17,7 +17,10 @@ struct RoundArgs {
     float *r[kMaxP];             // R_p arena bases (fp32)
     unsigned long long active;   // bit p: process p is on time in this round
     unsigned long long valid;    // bit p: R_p holds an undelivered gradient
-    unsigned long long passive;  // bit p: process p is late (p < P and not active)
+    unsigned long long gload;    // bit p: this launch reads G_p (all p < P when fused; only
+                                 // on-time processes when the carry runs as its own kernel)
+    unsigned long long store;    // bit p: this launch stores G_p into R_p (late processes when
+                                 // fused; none otherwise)
     const void *dummy;           // 16 readable bytes: stands in for streams not to be read
     float *w;                    // parameters (NULL: no update rule)
     float *v;                    // momentum
@@ -28,6 +31,16 @@ struct RoundArgs {
     float inv_P;                 // 1.0f / (float)P
     float neg_lr;                // -lr
     float mu;
+};
+
+// The carry as a kernel of its own: R_p <- G_p for every late process, one (source,
+// destination) pair after the other.
+struct CarryArgs {
+    const void *src[kMaxP];      // G_p arena bases of the late processes
+    float *dst[kMaxP];           // their R_p arena bases
+    int count;                   // number of pairs
+    long long e0;                // first element of the run
+    long long n;                 // elements in the run
 };
 
 struct SgdArgs {
@@ -46,11 +59,14 @@ struct Launch {
     int unroll = 1;        // 16-byte vectors per thread and iteration
     int nontemporal = 1;   // streaming hints on G and R
     int chunk = 0;         // ranks whose loads are in flight together; 0: chosen from P
+    int split = 0;         // 0: chosen from the round; 1: one fused kernel; 2: reduce+update
+                           // kernel followed by a carry (copy) kernel
     int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
 };
 
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
+hipError_t launch_carry(const CarryArgs &a, bool bf16, hipStream_t stream);
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

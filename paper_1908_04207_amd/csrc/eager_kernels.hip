@@ -99,7 +99,7 @@ __device__ __forceinline__ void round_vectors(const RoundArgs &a, const long lon
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
             const int p = p0 + j;
-            const bool real = p < a.P;
+            const bool real = (a.gload >> p) & 1ull;
             const char *gp = static_cast<const char *>(a.g[p]);
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -164,7 +164,7 @@ __device__ __forceinline__ void round_vectors(const RoundArgs &a, const long lon
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
             const int p = p0 + j;
-            if ((a.passive >> p) & 1ull) {
+            if ((a.store >> p) & 1ull) {
                 float *rp = a.r[p];
 #pragma unroll
                 for (int u = 0; u < U; ++u)
@@ -211,26 +211,30 @@ __device__ __forceinline__ void round_vectors(const RoundArgs &a, const long lon
 // Ragged tail (fewer elements than a vector): plain scalar code, fixed order in both
 // modes - at most 7 elements per launch.
 template <bool BF16>
+__device__ __forceinline__ float load_grad_scalar(const void *g, long long i)
+{
+    if (BF16) {
+        const unsigned short h = static_cast<const unsigned short *>(g)[i];
+        return __uint_as_float(static_cast<unsigned>(h) << 16);
+    }
+    return static_cast<const float *>(g)[i];
+}
+
+template <bool BF16>
 __device__ __forceinline__ void round_scalar(const RoundArgs &a, long long i)
 {
     float s = 0.0f;
     for (int p = 0; p < a.P; ++p) {
-        float g;
-        if (BF16) {
-            const unsigned short h = static_cast<const unsigned short *>(a.g[p])[i];
-            g = __uint_as_float(static_cast<unsigned>(h) << 16);
-        } else {
-            g = static_cast<const float *>(a.g[p])[i];
-        }
         const bool on_time = (a.active >> p) & 1ull;
         const bool has_stale = (a.valid >> p) & 1ull;
         if (on_time) {
+            const float g = load_grad_scalar<BF16>(a.g[p], i);
             float c = g;
             if (has_stale) c = a.r[p][i] + g;
             s = s + c;
         } else {
             if (has_stale) s = s + a.r[p][i];
-            a.r[p][i] = g;
+            if ((a.store >> p) & 1ull) a.r[p][i] = load_grad_scalar<BF16>(a.g[p], i);
         }
     }
     const float avg = s * a.inv_P;
@@ -269,6 +273,38 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs a)
     const long long rem = a.n - nvec * W;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
         round_scalar<BF16>(a, a.e0 + nvec * W + threadIdx.x);
+}
+
+// R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx is
+// pair-major), so that at any time the device streams one source and one destination.
+// A copy of few streams runs near the read-only rate on MI355X, whereas the same bytes
+// written as 8-31 interleaved streams next to the reduction's reads cost 10-15 %.
+template <bool BF16>
+__global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a, unsigned blocks_per_pair)
+{
+    constexpr int W = BF16 ? 8 : 4;
+    const unsigned pair = blockIdx.x / blocks_per_pair;
+    const unsigned blk = blockIdx.x - pair * blocks_per_pair;
+    const long long nvec = a.n / W;
+    const char *src = static_cast<const char *>(a.src[pair]);
+    float *dst = a.dst[pair];
+    const long long stride = static_cast<long long>(blocks_per_pair) * blockDim.x;
+    for (long long vi = static_cast<long long>(blk) * blockDim.x + threadIdx.x; vi < nvec;
+         vi += stride) {
+        const long long e = a.e0 + vi * W;
+        const u32x4 g = ld_u4<true>(src + e * (BF16 ? 2 : 4));
+        if (BF16) {
+            st_f4<true>(dst + e, widen_lo(g, 0));
+            st_f4<true>(dst + e + 4, widen_lo(g, 1));
+        } else {
+            st_f4<true>(dst + e, __builtin_bit_cast(f32x4, g));
+        }
+    }
+    const long long rem = a.n - nvec * W;
+    if (blk == 0 && static_cast<long long>(threadIdx.x) < rem) {
+        const long long i = a.e0 + nvec * W + threadIdx.x;
+        dst[i] = load_grad_scalar<BF16>(src, i);
+    }
 }
 
 template <bool FAST>
@@ -427,6 +463,23 @@ hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &
                     : launch_round_nt<true, false>(a, cfg, grid, stream);
     return fast ? launch_round_nt<false, true>(a, cfg, grid, stream)
                 : launch_round_nt<false, false>(a, cfg, grid, stream);
+}
+
+hipError_t launch_carry(const CarryArgs &a, bool bf16, hipStream_t stream)
+{
+    if (a.n <= 0 || a.count <= 0) return hipSuccess;
+    const long long nvec = a.n / (bf16 ? 8 : 4);
+    long long bpp = (nvec + 255) / 256;
+    if (bpp < 1) bpp = 1;
+    if (bpp > 0x7fffffffLL / a.count) bpp = 0x7fffffffLL / a.count;   // the kernel strides
+    const unsigned grid = static_cast<unsigned>(bpp) * static_cast<unsigned>(a.count);
+    if (bf16)
+        hipLaunchKernelGGL(carry_kernel<true>, dim3(grid), dim3(256), 0, stream, a,
+                           static_cast<unsigned>(bpp));
+    else
+        hipLaunchKernelGGL(carry_kernel<false>, dim3(grid), dim3(256), 0, stream, a,
+                           static_cast<unsigned>(bpp));
+    return hipGetLastError();
 }
 
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream)
