@@ -157,18 +157,25 @@ int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask);
 int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
 
 /*
- * Launch shape of the round kernel, for measurement sweeps.  Unknown keys: EINVAL.
- *   "block"      threads per workgroup: 64 (default), 128 or 256
- *   "max_blocks" 0 = one workgroup per tile; otherwise a cap, workgroups then stride
- *   "unroll"     16-byte vectors per thread and iteration: 1 or 2
- *   "nontemporal" 1 = streaming cache hints on G and R, 0 = plain loads and stores
- *   "split"      0 = chosen per round (default); 1 = one fused kernel; 2 = reduction + update
+ * Launch shape of the round kernels, for measurement sweeps.  Unknown keys: EINVAL.  A
+ * combination the library has no kernel for makes the next round fail with EDEVICE.
+ *   "compact"    fp32 gradients only: 1 (default) = only the streams a round needs are
+ *                listed and read (one 16-byte vector per lane, grid covers the range;
+ *                "unroll", "max_blocks" and "nontemporal" do not apply, "chunk" is 8 or
+ *                16); 0 = fixed rank chunks with cached stand-in loads (always used for
+ *                bf16 gradients)
+ *   "split"      0 = chosen per round (default: split when 8 or more processes are late,
+ *                fp32 compact path only); 1 = one fused kernel; 2 = reduction + update
  *                kernel followed by a copy kernel for the send buffers of late processes
- *   "chunk"      ranks whose loads are in flight together: 0 (chosen from P), 4, 8, 16, 32
- *                (32 only with fp32 gradients and unroll 1, 16 with bf16 gradients only
- *                with unroll 1; otherwise the launch fails with EDEVICE)
- *   "blocks_per_cu" 0 = chosen from P and block (default); -1 = no cap; 1..32 = at most
+ *   "block"      threads per workgroup: 64 (default), 128 or 256
+ *   "blocks_per_cu" 0 = chosen from the round (default); -1 = no cap; 1..32 = at most
  *                that many workgroups resident per CU
+ *   "chunk"      streams (ranks) whose loads are in flight together: 0 = default, 4, 8, 16,
+ *                32 (32 and, with bf16 gradients and unroll 2, 16 exist only in part)
+ *   "max_blocks" rank-chunk kernel: 0 = one workgroup per tile; otherwise a cap,
+ *                workgroups then stride
+ *   "unroll"     rank-chunk kernel: 16-byte vectors per thread and iteration: 1 or 2
+ *   "nontemporal" rank-chunk kernel: 1 = streaming cache hints on G and R, 0 = plain
  */
 int eager_set_launch(eager_ctx *ctx, const char *key, int value);
 

@@ -28,9 +28,32 @@ struct RoundArgs {
     long long e0;                // first element of the run (arena index)
     long long n;                 // elements in the run
     int P;
+    int elem_bytes;              // bytes per gradient element: 4 (fp32) or 2 (bf16)
     float inv_P;                 // 1.0f / (float)P
     float neg_lr;                // -lr
     float mu;
+};
+
+// The same round with the streams compacted (fp32 gradients only: G and R are then both
+// plain float streams).  Slot k is one stream and one action; slots are listed in the
+// order in which they enter the sum (ascending rank, send buffer before gradient):
+//   ADD    s = s + x                       (a pending R_p of a late process, or the G_p
+//                                           of an on-time process with an empty buffer)
+//   HOLD   c = x                           (R_p of an on-time process ...)
+//   PAIR   s = s + (c + x)                 (... followed by its G_p)
+//   STORE  dst <- x, nothing added         (G_p of a late process, fused mode only)
+// Streams that need not be read do not appear at all, so no load is wasted.
+constexpr int kMaxSlots = 2 * kMaxP;
+enum SlotKind { kAdd = 0, kHold = 1, kPair = 2, kStore = 3 };
+struct SlotArgs {
+    const float *src[kMaxSlots];
+    float *dst[kMaxSlots];             // meaningful for STORE slots only
+    unsigned long long kind0[2];       // bit k: low bit of the kind of slot k
+    unsigned long long kind1[2];       // bit k: high bit
+    int n_slots;
+    float *w, *v, *recv;
+    long long e0, n;
+    float inv_P, neg_lr, mu;
 };
 
 // The carry as a kernel of its own: R_p <- G_p for every late process, one (source,
@@ -59,6 +82,8 @@ struct Launch {
     int unroll = 1;        // 16-byte vectors per thread and iteration
     int nontemporal = 1;   // streaming hints on G and R
     int chunk = 0;         // ranks whose loads are in flight together; 0: chosen from P
+    int compact = 1;       // fp32 gradients: 1 = compacted stream list (slot kernel), 0 = rank
+                           // chunks with stand-in loads (always used for bf16 gradients)
     int split = 0;         // 0: chosen from the round; 1: one fused kernel; 2: reduce+update
                            // kernel followed by a carry (copy) kernel
     int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU

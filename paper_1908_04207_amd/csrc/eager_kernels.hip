@@ -25,6 +25,18 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Kernel arguments are read straight from the kernel-argument segment (constant address
+// space, scalar loads).  Going through the by-value parameter instead makes the compiler
+// keep a private copy of the whole struct in scratch memory as soon as it is indexed
+// dynamically in more places than its copy-elision looks at.
+typedef const RoundArgs __attribute__((address_space(4))) KRoundArgs;
+typedef const SlotArgs __attribute__((address_space(4))) KSlotArgs;
+template <typename T>
+__device__ __forceinline__ const T __attribute__((address_space(4))) &kernarg()
+{
+    return *(const T __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
 template <bool NT>
 __device__ __forceinline__ f32x4 ld_f4(const float *p)
 {
@@ -68,7 +80,7 @@ __device__ __forceinline__ f32x4 widen_lo(u32x4 x, int half)   // elements 0..3 
 // compiler can no longer count outstanding loads and falls back to waiting for each
 // one, which leaves a single load in flight per wavefront.
 template <bool BF16, bool FAST, bool NT, int U, int CH>
-__device__ __forceinline__ void round_vectors(const RoundArgs &a, const long long (&e)[U])
+__device__ __forceinline__ void round_vectors(KRoundArgs &a, const long long (&e)[U])
 {
     constexpr int NV = BF16 ? 2 : 1;
     constexpr int GB = BF16 ? 2 : 4;
@@ -221,7 +233,7 @@ __device__ __forceinline__ float load_grad_scalar(const void *g, long long i)
 }
 
 template <bool BF16>
-__device__ __forceinline__ void round_scalar(const RoundArgs &a, long long i)
+__device__ __forceinline__ void round_scalar(KRoundArgs &a, long long i)
 {
     float s = 0.0f;
     for (int p = 0; p < a.P; ++p) {
@@ -247,8 +259,9 @@ __device__ __forceinline__ void round_scalar(const RoundArgs &a, long long i)
 }
 
 template <bool BF16, bool FAST, bool NT, int U, int CH, int LB>
-__global__ __launch_bounds__(LB) void round_kernel(const RoundArgs a)
+__global__ __launch_bounds__(LB) void round_kernel(const RoundArgs)
 {
+    KRoundArgs &a = kernarg<RoundArgs>();
     constexpr int W = BF16 ? 8 : 4;
     const long long nvec = a.n / W;
     const long long tile = static_cast<long long>(blockDim.x) * U;
@@ -273,6 +286,170 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs a)
     const long long rem = a.n - nvec * W;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
         round_scalar<BF16>(a, a.e0 + nvec * W + threadIdx.x);
+}
+
+// ---------------------------------------------------------------------------------------
+// Compacted form for fp32 gradients: a list of float streams ("slots"), each with one
+// action, in summation order.  A chunk of C slots is C loads issued back to back, then
+// the adds, then the stores; the list is consumed in chunks of CH and a remainder of
+// CH/2, CH/4, ... 1, so that not a single stand-in load is issued.
+template <bool FAST, bool NT, int U, int C>
+__device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const long long (&e)[U],
+                                           f32x4 (&s)[U][2], f32x4 (&hold)[U])
+{
+    f32x4 x[U][C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        const float *sp = a.src[k0 + j];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u][j] = ld_f4<NT>(sp + e[u]);
+    }
+    const unsigned long long b0 = a.kind0[k0 >> 6] >> (k0 & 63);
+    const unsigned long long b1 = a.kind1[k0 >> 6] >> (k0 & 63);
+    // Every loaded value is used unconditionally (selects on scalar conditions, not
+    // branches): if a path existed on which a load is never consumed, the compiler would
+    // have to drain all memory operations before its registers could be reused.
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        const bool lo = (b0 >> j) & 1ull, hi = (b1 >> j) & 1ull;
+        const bool is_add = !lo && !hi, is_hold = lo && !hi, is_pair = !lo && hi;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (FAST) {
+                // any order: two interleaved partial sums
+                const f32x4 t = s[u][j & 1] + x[u][j];
+                s[u][j & 1] = (lo && hi) ? s[u][j & 1] : t;
+            } else {
+                const f32x4 pair = hold[u] + x[u][j];
+                const f32x4 c = is_pair ? pair : x[u][j];
+                const f32x4 t = s[u][0] + c;
+                s[u][0] = (is_add || is_pair) ? t : s[u][0];
+                hold[u] = is_hold ? x[u][j] : hold[u];
+            }
+        }
+    }
+    // Stores stay behind the adds: moved ahead of them (the compiler likes to sink the add
+    // chain below the store branches), the in-order memory counter would make every add
+    // wait for the acknowledgement of a store instead of for its load.  The empty
+    // statement pins the sums here and orders the stores after it.
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        asm volatile("" : "+v"(s[u][0]), "+v"(s[u][1]), "+v"(hold[u]) : : "memory");
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        if (((b0 >> j) & 1ull) && ((b1 >> j) & 1ull)) {          // STORE
+            float *dp = a.dst[k0 + j];
+#pragma unroll
+            for (int u = 0; u < U; ++u) st_f4<NT>(dp + e[u], x[u][j]);
+        }
+    }
+}
+
+template <bool FAST, bool NT, int U, int R>
+__device__ __forceinline__ void slot_remainder(KSlotArgs &a, int k0, int rem,
+                                               const long long (&e)[U], f32x4 (&s)[U][2],
+                                               f32x4 (&hold)[U])
+{
+    if constexpr (R >= 1) {
+        if (rem == R) slot_chunk<FAST, NT, U, R>(a, k0, e, s, hold);
+        else slot_remainder<FAST, NT, U, R - 1>(a, k0, rem, e, s, hold);
+    }
+}
+
+template <bool FAST, bool NT, int U, int CH>
+__device__ __forceinline__ void slot_vectors(KSlotArgs &a, const long long (&e)[U])
+{
+    f32x4 s[U][2], hold[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        s[u][0] = (f32x4)(0.0f);
+        s[u][1] = (f32x4)(0.0f);
+        hold[u] = (f32x4)(0.0f);
+    }
+    f32x4 vo[U], wo[U];
+    if (a.w) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            vo[u] = ld_f4<false>(a.v + e[u]);
+            wo[u] = ld_f4<false>(a.w + e[u]);
+        }
+    }
+    // The chunk sequence is unrolled to its maximum length with forward exits only: in a
+    // real loop the compiler drains every outstanding store at the loop head before the
+    // next chunk's loads may issue, which puts a store round trip between chunks.
+    const int n = a.n_slots;
+#pragma unroll
+    for (int c = 0; c < kMaxSlots / CH; ++c)
+        if ((c + 1) * CH <= n) slot_chunk<FAST, NT, U, CH>(a, c * CH, e, s, hold);
+    // the remainder is ONE chunk of its exact size: every chunk costs a memory round
+    // trip per wavefront, so a cascade of smaller and smaller chunks would be slow
+    slot_remainder<FAST, NT, U, CH - 1>(a, n / CH * CH, n % CH, e, s, hold);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        f32x4 sum = s[u][0];
+        if (FAST) sum = sum + s[u][1];
+        const f32x4 avg = sum * a.inv_P;
+        if (a.recv) st_f4<false>(a.recv + e[u], avg);
+        if (a.w) {
+            f32x4 vn, wn;
+            if (FAST) {
+#pragma clang fp contract(fast)
+                vn = a.mu * vo[u] + avg;
+                wn = a.neg_lr * vn + wo[u];
+            } else {
+                vn.x = __builtin_fmaf(a.mu, vo[u].x, avg.x);
+                vn.y = __builtin_fmaf(a.mu, vo[u].y, avg.y);
+                vn.z = __builtin_fmaf(a.mu, vo[u].z, avg.z);
+                vn.w = __builtin_fmaf(a.mu, vo[u].w, avg.w);
+                wn.x = __builtin_fmaf(a.neg_lr, vn.x, wo[u].x);
+                wn.y = __builtin_fmaf(a.neg_lr, vn.y, wo[u].y);
+                wn.z = __builtin_fmaf(a.neg_lr, vn.z, wo[u].z);
+                wn.w = __builtin_fmaf(a.neg_lr, vn.w, wo[u].w);
+            }
+            st_f4<false>(a.v + e[u], vn);
+            st_f4<false>(a.w + e[u], wn);
+        }
+    }
+}
+
+// ragged tail: at most 3 elements per launch, fixed order in both modes
+__device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
+{
+    float s = 0.0f, hold = 0.0f;
+    for (int k = 0; k < a.n_slots; ++k) {
+        const int kind = static_cast<int>((a.kind0[k >> 6] >> (k & 63)) & 1ull) |
+                         static_cast<int>(((a.kind1[k >> 6] >> (k & 63)) & 1ull) << 1);
+        const float x = a.src[k][i];
+        if (kind == kAdd) s = s + x;
+        else if (kind == kHold) hold = x;
+        else if (kind == kPair) { const float c = hold + x; s = s + c; }
+        else a.dst[k][i] = x;
+    }
+    const float avg = s * a.inv_P;
+    if (a.recv) a.recv[i] = avg;
+    if (a.w) {
+        const float vn = __builtin_fmaf(a.mu, a.v[i], avg);
+        a.v[i] = vn;
+        a.w[i] = __builtin_fmaf(a.neg_lr, vn, a.w[i]);
+    }
+}
+
+// One 16-byte vector per lane and no loop over tiles: inside a loop every scalar condition
+// of every slot is loop invariant, the compiler hoists hundreds of them out of it and then
+// spills scalar registers.  The grid always covers the run.
+template <bool FAST, bool NT, int CH>
+__global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
+{
+    KSlotArgs &a = kernarg<SlotArgs>();
+    const long long nvec = a.n / 4;
+    const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vi < nvec) {
+        const long long e[1] = {a.e0 + vi * 4};
+        slot_vectors<FAST, NT, 1, CH>(a, e);
+    }
+    const long long rem = a.n - nvec * 4;
+    if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
+        slot_scalar(a, a.e0 + nvec * 4 + threadIdx.x);
 }
 
 // R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx is
@@ -372,21 +549,20 @@ __global__ __launch_bounds__(256) void read_kernel(const f32x4 *src, long long n
 constexpr int kLdsPerCu = 160 * 1024;
 
 // Resident workgroups per CU when the caller leaves the choice to the library: measured
-// optima with 64-thread workgroups for 1, 2 and 4 rank chunks of 8.
-int auto_blocks_per_cu(int P, int block)
+// optima of the rank-chunk kernel with 64-thread workgroups for 1, 2 and 4 chunks of 8.
+int auto_blocks_per_cu(int P, int block, bool bf16)
 {
     const int chunks = (P + 7) / 8;
-    const int waves = chunks <= 1 ? 10 : chunks == 2 ? 5 : 6;
+    const int waves = chunks <= 1 ? 10 : chunks == 2 ? (bf16 ? 8 : 5) : 6;
     const int b = (waves * 64 + block - 1) / block;
     return b < 1 ? 1 : b;
 }
 
-template <typename K>
-hipError_t launch_capped(K kernel, const RoundArgs &a, const Launch &cfg, unsigned grid,
+template <typename K, typename A>
+hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, unsigned grid,
                          hipStream_t st)
 {
     unsigned lds = 0;
-    const int bpc = cfg.blocks_per_cu == 0 ? auto_blocks_per_cu(a.P, cfg.block) : cfg.blocks_per_cu;
     if (bpc > 0) {
         lds = static_cast<unsigned>(kLdsPerCu / bpc) & ~2047u;
         static bool raised = false;   // one flag per kernel instantiation
@@ -400,6 +576,89 @@ hipError_t launch_capped(K kernel, const RoundArgs &a, const Launch &cfg, unsign
     }
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(cfg.block), lds, st, a);
     return hipGetLastError();
+}
+
+template <typename K>
+hipError_t launch_capped(K kernel, const RoundArgs &a, const Launch &cfg, unsigned grid,
+                         hipStream_t st)
+{
+    const bool bf16 = a.elem_bytes == 2;
+    const int bpc = cfg.blocks_per_cu == 0 ? auto_blocks_per_cu(a.P, cfg.block, bf16)
+                                           : cfg.blocks_per_cu;
+    return launch_capped(kernel, a, bpc, cfg, grid, st);
+}
+
+// ---- slot kernel: build the stream list from the rank masks, pick the instantiation
+void build_slots(const RoundArgs &a, SlotArgs &s)
+{
+    s.n_slots = 0;
+    s.kind0[0] = s.kind0[1] = s.kind1[0] = s.kind1[1] = 0;
+    auto push = [&s](const float *src, float *dst, int kind) {
+        const int k = s.n_slots++;
+        s.src[k] = src;
+        s.dst[k] = dst;
+        if (kind & 1) s.kind0[k >> 6] |= 1ull << (k & 63);
+        if (kind & 2) s.kind1[k >> 6] |= 1ull << (k & 63);
+    };
+    for (int p = 0; p < a.P; ++p) {
+        const bool on_time = (a.active >> p) & 1ull, has_stale = (a.valid >> p) & 1ull;
+        const float *g = static_cast<const float *>(a.g[p]);
+        if (on_time) {
+            if (has_stale) {
+                push(a.r[p], nullptr, kHold);
+                push(g, nullptr, kPair);
+            } else {
+                push(g, nullptr, kAdd);
+            }
+        } else {
+            if (has_stale) push(a.r[p], nullptr, kAdd);
+            if ((a.store >> p) & 1ull) push(g, a.r[p], kStore);
+        }
+    }
+    s.w = a.w;
+    s.v = a.v;
+    s.recv = a.recv;
+    s.e0 = a.e0;
+    s.n = a.n;
+    s.inv_P = a.inv_P;
+    s.neg_lr = a.neg_lr;
+    s.mu = a.mu;
+}
+
+// Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of
+// late gradients in the same pass few wavefronts are best once there are many streams;
+// a pass that only reads (apart from w and v) likes more.
+int auto_waves_for_slots(int n_slots, bool has_stores)
+{
+    if (has_stores) return n_slots <= 14 ? 8 : 5;
+    return n_slots <= 20 ? 10 : 6;
+}
+
+template <bool FAST>
+hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
+{
+    SlotArgs s;
+    build_slots(a, s);
+    int bpc = cfg.blocks_per_cu;
+    if (bpc == 0) {
+        bpc = (auto_waves_for_slots(s.n_slots, a.store != 0) * 64 + cfg.block - 1) / cfg.block;
+        if (bpc < 1) bpc = 1;
+    }
+    // one vector per lane, the grid covers the run ("unroll" and "max_blocks" do not apply);
+    // always nontemporal (the A/B against plain loads and stores lives in the rank-chunk
+    // kernel)
+    const long long nvec = s.n / 4;
+    long long g = (nvec + cfg.block - 1) / cfg.block;
+    if (g < 1) g = 1;
+    if (g > 0x7fffffffLL) return hipErrorInvalidValue;
+    const unsigned grid = static_cast<unsigned>(g);
+    int ch = cfg.chunk;
+    if (ch == 0) ch = 16;
+    switch (ch) {
+    case 8: return launch_capped(slot_kernel<FAST, true, 8>, s, bpc, cfg, grid, st);
+    case 16: return launch_capped(slot_kernel<FAST, true, 16>, s, bpc, cfg, grid, st);
+    default: return hipErrorInvalidValue;   // more streams per chunk exceed the scalar registers
+    }
 }
 
 template <bool BF16, bool FAST, bool NT, int U>
@@ -461,6 +720,8 @@ hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &
     if (bf16)
         return fast ? launch_round_nt<true, true>(a, cfg, grid, stream)
                     : launch_round_nt<true, false>(a, cfg, grid, stream);
+    if (cfg.compact)
+        return fast ? launch_slots<true>(a, cfg, stream) : launch_slots<false>(a, cfg, stream);
     return fast ? launch_round_nt<false, true>(a, cfg, grid, stream)
                 : launch_round_nt<false, false>(a, cfg, grid, stream);
 }

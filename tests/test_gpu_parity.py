@@ -134,18 +134,18 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
     cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 3), 40000)
     bt = cfg.buckets
     ref = None
-    for block, unroll, maxb, nt, chunk, bpc, split in [
-            (256, 1, 0, 1, 0, 0, 1), (64, 2, 0, 1, 4, 4, 2), (128, 1, 3, 0, 16, 2, 1),
-            (256, 1, 0, 1, 16, 1, 2), (256, 2, 7, 0, 8, 3, 0),
-            (64, 1, 2, 1, 32 if dtype == "f32" else 16, 5, 2)]:
+    for block, unroll, maxb, nt, chunk, bpc, split, compact in [
+            (256, 1, 0, 1, 0, 0, 1, 1), (64, 2, 0, 1, 4, 4, 2, 0), (128, 1, 3, 0, 16, 2, 1, 1),
+            (256, 1, 0, 1, 16, 1, 2, 1), (256, 2, 7, 0, 8, 3, 0, 1), (64, 2, 0, 1, 8, -1, 2, 1),
+            (64, 1, 2, 1, 32 if dtype == "f32" else 16, 5, 2, 0)]:
         pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, seed=4)
         for key, val in (("block", block), ("unroll", unroll), ("max_blocks", maxb),
                          ("nontemporal", nt), ("chunk", chunk), ("blocks_per_cu", bpc),
-                         ("split", split)):
+                         ("split", split), ("compact", compact)):
             pair.ctx.eager_set_launch(key, val)
         for t in range(3):
             pair.round(plan_for(eb, cfg, t), pair.fresh_grads(t))
-        pair.compare(exact=True, what=f"launch {block}/{unroll}/{maxb}/{nt}/{chunk}/{bpc}/{split}")
+        pair.compare(exact=True, what=f"launch {block}/{unroll}/{maxb}/{nt}/{chunk}/{bpc}/{split}/{compact}")
         torch.cuda.synchronize()
         if ref is None:
             ref = pair.w.clone()
