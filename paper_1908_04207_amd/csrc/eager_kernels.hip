@@ -630,7 +630,7 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
 // a pass that only reads (apart from w and v) likes more.
 int auto_waves_for_slots(int n_slots, bool has_stores)
 {
-    if (has_stores) return n_slots <= 14 ? 8 : 5;
+    if (has_stores) return n_slots <= 16 ? 8 : 5;   // one chunk of 16 or several
     return n_slots <= 20 ? 10 : 6;
 }
 
