@@ -159,14 +159,21 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
 /*
  * Launch shape of the round kernels, for measurement sweeps.  Unknown keys: EINVAL.  A
  * combination the library has no kernel for makes the next round fail with EDEVICE.
- *   "compact"    fp32 gradients only: 1 (default) = only the streams a round needs are
- *                listed and read (one 16-byte vector per lane, grid covers the range;
- *                "unroll", "max_blocks" and "nontemporal" do not apply, "chunk" is 8 or
- *                16); 0 = fixed rank chunks with cached stand-in loads (always used for
- *                bf16 gradients)
- *   "split"      0 = chosen per round (default: split when 8 or more processes are late,
- *                fp32 compact path only); 1 = one fused kernel; 2 = reduction + update
- *                kernel followed by a copy kernel for the send buffers of late processes
+ *   "compact"    1 (default) = only the streams a round needs are listed and read (one
+ *                group of 4 elements per lane, grid covers the range; "unroll",
+ *                "max_blocks" and "nontemporal" do not apply, "chunk" is 8 or 16);
+ *                0 = fixed rank chunks with cached stand-in loads
+ *   "split"      0 = chosen per round (default: fp32 gradients on the compact path are split
+ *                when 8 or more processes are late, or when somebody is late and the fused
+ *                pass would have more than 16 streams); 1 = one fused kernel; 2 = reduction +
+ *                update kernel followed by a copy kernel for the send buffers of late processes
+ *   "nt_state"   compact path: nontemporal hint on w, v and recv too: -1 (default) = when
+ *                they exceed 256 MiB in the call (they cannot stay in the last-level cache
+ *                until the next round), 0 = never, 1 = always
+ *   "carry_block", "carry_vec", "carry_blocks_per_cu"  shape of the copy kernel of a split
+ *                round: threads per workgroup (64 default, 128, 256), groups of 4 elements
+ *                per thread (1 default, 2, 4), resident workgroups per CU (-1 = no cap,
+ *                default; 1..32)
  *   "block"      threads per workgroup: 64 (default), 128 or 256
  *   "blocks_per_cu" 0 = chosen from the round (default); -1 = no cap; 1..32 = at most
  *                that many workgroups resident per CU

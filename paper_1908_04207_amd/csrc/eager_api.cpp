@@ -58,16 +58,22 @@ uint64_t initiator_hash(uint64_t seed, uint64_t step)
 
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
 // the reduction instead of inside it.
-bool use_split(const eager::Launch &l, bool bf16, int n_late)
+bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid)
 {
     if (l.split == 1) return false;
     if (l.split == 2) return true;
-    // Measured: with 8 or more late processes the copy of their gradients runs faster on
-    // its own (a copy of two streams at a time reaches 6.5 TB/s, the same bytes written
-    // as many interleaved streams next to the reduction's reads cost 5-7 % of the round).
-    // The bf16 rank-chunk kernel cannot drop the streams it does not need, so there the
-    // fused pass stays the faster one.
-    return !bf16 && l.compact != 0 && n_late >= 8;
+    // Measured on MI355X: a copy that streams one source and one destination at a time
+    // reaches 6.5 TB/s, whereas the same bytes written as many interleaved streams next to
+    // the reduction's reads cost 5-10 % of the round.  The fused pass wins only while all
+    // of its streams fit one chunk of 16 loads (one memory round trip per wavefront).  The
+    // rank-chunk kernel cannot drop the streams it does not need, and with bf16 gradients
+    // the fused pass is the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter
+    // configuration).
+    if (bf16 || l.compact == 0) return false;
+    const uint64_t late = ~mask & low_bits(P);
+    const int n_late = popcount64(late);
+    const int fused_streams = P + popcount64(valid);   // every G_p, every non-empty R_p
+    return n_late >= 8 || (n_late >= 1 && fused_streams > 16);
 }
 
 int check_range(eager_ctx *ctx, int b0, int b1)
@@ -149,7 +155,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
         a.dummy = static_cast<const char *>(grads[0]) + a.e0 * (ctx->bf16 ? 2 : 4);
         const uint64_t late = ~plan->mask & low_bits(P);
-        const bool split = late != 0 && use_split(ctx->launch, ctx->bf16, popcount64(late));
+        const bool split = late != 0 && use_split(ctx->launch, ctx->bf16, P, plan->mask, a.valid);
         a.gload = split ? plan->mask : low_bits(P);
         a.store = split ? 0 : late;
         hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
@@ -168,7 +174,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
                 }
             c.e0 = a.e0;
             c.n = a.n;
-            he = eager::launch_carry(c, ctx->bf16, static_cast<hipStream_t>(stream));
+            he = eager::launch_carry(c, ctx->bf16, ctx->launch, static_cast<hipStream_t>(stream));
             if (he != hipSuccess)
                 return fail(ctx, EAGER_EDEVICE, "carry kernel launch failed: %s",
                             hipGetErrorString(he));
@@ -374,6 +380,21 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
     } else if (!std::strcmp(key, "blocks_per_cu")) {
         if (value < -1 || value > 32) return fail(ctx, EAGER_EINVAL, "blocks_per_cu must be -1..32");
         ctx->launch.blocks_per_cu = value;
+    } else if (!std::strcmp(key, "nt_state")) {
+        if (value < -1 || value > 1) return fail(ctx, EAGER_EINVAL, "nt_state must be -1, 0 or 1");
+        ctx->launch.nt_state = value;
+    } else if (!std::strcmp(key, "carry_block")) {
+        if (value != 64 && value != 128 && value != 256)
+            return fail(ctx, EAGER_EINVAL, "carry_block must be 64, 128 or 256");
+        ctx->launch.carry_block = value;
+    } else if (!std::strcmp(key, "carry_vec")) {
+        if (value != 1 && value != 2 && value != 4)
+            return fail(ctx, EAGER_EINVAL, "carry_vec must be 1, 2 or 4");
+        ctx->launch.carry_vec = value;
+    } else if (!std::strcmp(key, "carry_blocks_per_cu")) {
+        if (value < -1 || value == 0 || value > 32)
+            return fail(ctx, EAGER_EINVAL, "carry_blocks_per_cu must be -1 or 1..32");
+        ctx->launch.carry_blocks_per_cu = value;
     } else {
         return fail(ctx, EAGER_EINVAL, "unknown launch key '%s'", key);
     }

@@ -34,22 +34,25 @@ struct RoundArgs {
     float mu;
 };
 
-// The same round with the streams compacted (fp32 gradients only: G and R are then both
-// plain float streams).  Slot k is one stream and one action; slots are listed in the
-// order in which they enter the sum (ascending rank, send buffer before gradient):
+// The same round with the streams compacted.  Slot k is one stream and one action; slots are
+// listed in the order in which they enter the sum (ascending rank, send buffer before
+// gradient):
 //   ADD    s = s + x                       (a pending R_p of a late process, or the G_p
 //                                           of an on-time process with an empty buffer)
 //   HOLD   c = x                           (R_p of an on-time process ...)
 //   PAIR   s = s + (c + x)                 (... followed by its G_p)
 //   STORE  dst <- x, nothing added         (G_p of a late process, fused mode only)
-// Streams that need not be read do not appear at all, so no load is wasted.
+// Streams that need not be read do not appear at all, so no load is wasted.  A stream is
+// fp32 (send buffers; fp32 gradients) or bf16 (bf16 gradients); a lane owns 4 consecutive
+// elements of every stream either way.
 constexpr int kMaxSlots = 2 * kMaxP;
 enum SlotKind { kAdd = 0, kHold = 1, kPair = 2, kStore = 3 };
 struct SlotArgs {
-    const float *src[kMaxSlots];
+    const void *src[kMaxSlots];        // arena bases
     float *dst[kMaxSlots];             // meaningful for STORE slots only
     unsigned long long kind0[2];       // bit k: low bit of the kind of slot k
     unsigned long long kind1[2];       // bit k: high bit
+    unsigned long long bf[2];          // bit k: the stream of slot k is bf16
     int n_slots;
     float *w, *v, *recv;
     long long e0, n;
@@ -87,11 +90,15 @@ struct Launch {
     int split = 0;         // 0: chosen from the round; 1: one fused kernel; 2: reduce+update
                            // kernel followed by a carry (copy) kernel
     int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
+    int nt_state = -1;     // w, v, recv nontemporal: -1 chosen from their size, 0 no, 1 yes
+    int carry_block = 64;  // carry kernel: threads per workgroup
+    int carry_vec = 1;     // carry kernel: lane-vectors per thread and iteration (1, 2, 4)
+    int carry_blocks_per_cu = -1;  // carry kernel: -1 no cap, else max workgroups per CU
 };
 
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
-hipError_t launch_carry(const CarryArgs &a, bool bf16, hipStream_t stream);
+hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream);
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

@@ -19,11 +19,15 @@
 //     defined bit for bit; fast mode sums a chunk as a tree and lets the compiler fuse.
 #include "eager_internal.h"
 
+#include <mutex>
+#include <set>
+
 namespace eager {
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // Kernel arguments are read straight from the kernel-argument segment (constant address
 // space, scalar loads).  Going through the by-value parameter instead makes the compiler
@@ -289,32 +293,66 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs)
 }
 
 // ---------------------------------------------------------------------------------------
-// Compacted form for fp32 gradients: a list of float streams ("slots"), each with one
-// action, in summation order.  A chunk of C slots is C loads issued back to back, then
-// the adds, then the stores; the list is consumed in chunks of CH and a remainder of
-// CH/2, CH/4, ... 1, so that not a single stand-in load is issued.
-template <bool FAST, bool NT, int U, int C>
-__device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const long long (&e)[U],
+// Compacted form: a list of streams ("slots"), each with one action, in summation order.  A
+// chunk of C slots is C loads issued back to back, then the adds, then the stores; the list
+// is consumed in chunks of CH and one remainder chunk of its exact size, so that not a
+// single stand-in load is issued.
+//
+// A lane owns 4 consecutive elements of every stream, so that each load or store instruction
+// of a wavefront covers one contiguous kilobyte of an fp32 stream.  With bf16 gradients
+// (BF16) the lane's 4 gradient elements are 8 bytes, one half of an aligned 16-byte piece:
+// lanes 2k and 2k+1 load the same piece and each keeps its half.  That way every load of a
+// chunk is the same 16-byte instruction whatever the type of its stream - the type, like the
+// action, is a scalar select and never a branch around a load.
+struct LaneVec {
+    long long e;        // first of the lane's 4 elements (arena index)
+    long long off_bf;   // byte offset of the 16-byte piece of a bf16 stream that holds them
+    bool odd;           // the lane's elements are the upper half of that piece
+};
+
+template <bool BF16>
+__device__ __forceinline__ f32x4 slot_value(u32x4 raw, bool is_bf, bool odd)
+{
+    const f32x4 plain = __builtin_bit_cast(f32x4, raw);
+    if (!BF16) return plain;
+    const unsigned a = odd ? raw.z : raw.x, b = odd ? raw.w : raw.y;
+    f32x4 wide;
+    wide.x = __uint_as_float(a << 16);
+    wide.y = __uint_as_float(a & 0xffff0000u);
+    wide.z = __uint_as_float(b << 16);
+    wide.w = __uint_as_float(b & 0xffff0000u);
+    return is_bf ? wide : plain;
+}
+
+template <bool BF16, bool FAST, bool NT, int U, int C>
+__device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const LaneVec (&lv)[U],
                                            f32x4 (&s)[U][2], f32x4 (&hold)[U])
 {
-    f32x4 x[U][C];
-#pragma unroll
-    for (int j = 0; j < C; ++j) {
-        const float *sp = a.src[k0 + j];
-#pragma unroll
-        for (int u = 0; u < U; ++u) x[u][j] = ld_f4<NT>(sp + e[u]);
-    }
+    // a chunk starts at a multiple of 8 or 16 and holds at most 16 slots: its bits never
+    // straddle a mask word
     const unsigned long long b0 = a.kind0[k0 >> 6] >> (k0 & 63);
     const unsigned long long b1 = a.kind1[k0 >> 6] >> (k0 & 63);
+    const unsigned long long bf = BF16 ? a.bf[k0 >> 6] >> (k0 & 63) : 0ull;
+    u32x4 raw[U][C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        const char *sp = static_cast<const char *>(a.src[k0 + j]);
+        const bool is_bf = BF16 && ((bf >> j) & 1ull);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            raw[u][j] = ld_u4<NT>(sp + (is_bf ? lv[u].off_bf : lv[u].e * 4));
+    }
     // Every loaded value is used unconditionally (selects on scalar conditions, not
     // branches): if a path existed on which a load is never consumed, the compiler would
     // have to drain all memory operations before its registers could be reused.
+    f32x4 x[U][C];
 #pragma unroll
     for (int j = 0; j < C; ++j) {
         const bool lo = (b0 >> j) & 1ull, hi = (b1 >> j) & 1ull;
         const bool is_add = !lo && !hi, is_hold = lo && !hi, is_pair = !lo && hi;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            x[u][j] = slot_value<BF16>(raw[u][j], (bf >> j) & 1ull, lv[u].odd);
             if (FAST) {
                 // any order: two interleaved partial sums
                 const f32x4 t = s[u][j & 1] + x[u][j];
@@ -340,24 +378,26 @@ __device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const long long
         if (((b0 >> j) & 1ull) && ((b1 >> j) & 1ull)) {          // STORE
             float *dp = a.dst[k0 + j];
 #pragma unroll
-            for (int u = 0; u < U; ++u) st_f4<NT>(dp + e[u], x[u][j]);
+            for (int u = 0; u < U; ++u) st_f4<NT>(dp + lv[u].e, x[u][j]);
         }
     }
 }
 
-template <bool FAST, bool NT, int U, int R>
+template <bool BF16, bool FAST, bool NT, int U, int R>
 __device__ __forceinline__ void slot_remainder(KSlotArgs &a, int k0, int rem,
-                                               const long long (&e)[U], f32x4 (&s)[U][2],
+                                               const LaneVec (&lv)[U], f32x4 (&s)[U][2],
                                                f32x4 (&hold)[U])
 {
     if constexpr (R >= 1) {
-        if (rem == R) slot_chunk<FAST, NT, U, R>(a, k0, e, s, hold);
-        else slot_remainder<FAST, NT, U, R - 1>(a, k0, rem, e, s, hold);
+        if (rem == R) slot_chunk<BF16, FAST, NT, U, R>(a, k0, lv, s, hold);
+        else slot_remainder<BF16, FAST, NT, U, R - 1>(a, k0, rem, lv, s, hold);
     }
 }
 
-template <bool FAST, bool NT, int U, int CH>
-__device__ __forceinline__ void slot_vectors(KSlotArgs &a, const long long (&e)[U])
+// NTS: parameters, momentum and the receive buffer are streamed with the nontemporal hint
+// too (right when they are too large to stay in the last-level cache until the next round).
+template <bool BF16, bool FAST, bool NT, bool NTS, int U, int CH>
+__device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U])
 {
     f32x4 s[U][2], hold[U];
 #pragma unroll
@@ -370,8 +410,8 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const long long (&e)[
     if (a.w) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            vo[u] = ld_f4<false>(a.v + e[u]);
-            wo[u] = ld_f4<false>(a.w + e[u]);
+            vo[u] = ld_f4<NTS>(a.v + lv[u].e);
+            wo[u] = ld_f4<NTS>(a.w + lv[u].e);
         }
     }
     // The chunk sequence is unrolled to its maximum length with forward exits only: in a
@@ -380,16 +420,17 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const long long (&e)[
     const int n = a.n_slots;
 #pragma unroll
     for (int c = 0; c < kMaxSlots / CH; ++c)
-        if ((c + 1) * CH <= n) slot_chunk<FAST, NT, U, CH>(a, c * CH, e, s, hold);
+        if ((c + 1) * CH <= n) slot_chunk<BF16, FAST, NT, U, CH>(a, c * CH, lv, s, hold);
     // the remainder is ONE chunk of its exact size: every chunk costs a memory round
     // trip per wavefront, so a cascade of smaller and smaller chunks would be slow
-    slot_remainder<FAST, NT, U, CH - 1>(a, n / CH * CH, n % CH, e, s, hold);
+    slot_remainder<BF16, FAST, NT, U, CH - 1>(a, n / CH * CH, n % CH, lv, s, hold);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        const long long e = lv[u].e;
         f32x4 sum = s[u][0];
         if (FAST) sum = sum + s[u][1];
         const f32x4 avg = sum * a.inv_P;
-        if (a.recv) st_f4<false>(a.recv + e[u], avg);
+        if (a.recv) st_f4<NTS>(a.recv + e, avg);
         if (a.w) {
             f32x4 vn, wn;
             if (FAST) {
@@ -406,20 +447,26 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const long long (&e)[
                 wn.z = __builtin_fmaf(a.neg_lr, vn.z, wo[u].z);
                 wn.w = __builtin_fmaf(a.neg_lr, vn.w, wo[u].w);
             }
-            st_f4<false>(a.v + e[u], vn);
-            st_f4<false>(a.w + e[u], wn);
+            st_f4<NTS>(a.v + e, vn);
+            st_f4<NTS>(a.w + e, wn);
         }
     }
 }
 
-// ragged tail: at most 3 elements per launch, fixed order in both modes
+// ragged tail: at most 3 (7 with bf16 gradients) elements per launch, fixed order in both
+// modes
+template <bool BF16>
 __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
 {
     float s = 0.0f, hold = 0.0f;
     for (int k = 0; k < a.n_slots; ++k) {
         const int kind = static_cast<int>((a.kind0[k >> 6] >> (k & 63)) & 1ull) |
                          static_cast<int>(((a.kind1[k >> 6] >> (k & 63)) & 1ull) << 1);
-        const float x = a.src[k][i];
+        float x;
+        if (BF16 && ((a.bf[k >> 6] >> (k & 63)) & 1ull))
+            x = load_grad_scalar<true>(a.src[k], i);
+        else
+            x = load_grad_scalar<false>(a.src[k], i);
         if (kind == kAdd) s = s + x;
         else if (kind == kHold) hold = x;
         else if (kind == kPair) { const float c = hold + x; s = s + c; }
@@ -434,52 +481,81 @@ __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
     }
 }
 
-// One 16-byte vector per lane and no loop over tiles: inside a loop every scalar condition
-// of every slot is loop invariant, the compiler hoists hundreds of them out of it and then
+// Lane-vectors (groups of 4 elements) of a run that the vector path covers.  With bf16
+// gradients two lanes share one 16-byte piece, so the vector path ends at a multiple of 8
+// elements and never reads beyond the run.
+template <bool BF16>
+__host__ __device__ __forceinline__ long long slot_nvec(long long n)
+{
+    return BF16 ? (n / 8) * 2 : n / 4;
+}
+
+// One lane-vector per lane and no loop over tiles: inside a loop every scalar condition of
+// every slot is loop invariant, the compiler hoists hundreds of them out of it and then
 // spills scalar registers.  The grid always covers the run.
-template <bool FAST, bool NT, int CH>
+template <bool BF16, bool FAST, bool NT, bool NTS, int CH>
 __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
 {
     KSlotArgs &a = kernarg<SlotArgs>();
-    const long long nvec = a.n / 4;
+    const long long nvec = slot_nvec<BF16>(a.n);
     const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (vi < nvec) {
-        const long long e[1] = {a.e0 + vi * 4};
-        slot_vectors<FAST, NT, 1, CH>(a, e);
+        // bucket starts are multiples of 8 elements with bf16 gradients, so e0 * 2 is a
+        // multiple of 16 bytes
+        const LaneVec lv[1] = {{a.e0 + vi * 4, a.e0 * 2 + (vi >> 1) * 16, (vi & 1) != 0}};
+        slot_vectors<BF16, FAST, NT, NTS, 1, CH>(a, lv);
     }
     const long long rem = a.n - nvec * 4;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
-        slot_scalar(a, a.e0 + nvec * 4 + threadIdx.x);
+        slot_scalar<BF16>(a, a.e0 + nvec * 4 + threadIdx.x);
 }
 
 // R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx is
 // pair-major), so that at any time the device streams one source and one destination.
 // A copy of few streams runs near the read-only rate on MI355X, whereas the same bytes
 // written as 8-31 interleaved streams next to the reduction's reads cost 10-15 %.
-template <bool BF16>
+// A lane owns 4 elements: every store instruction of a wavefront writes one contiguous
+// kilobyte (a bf16 source is read 8 bytes per lane and widened).
+template <bool BF16, int V>
 __global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a, unsigned blocks_per_pair)
 {
-    constexpr int W = BF16 ? 8 : 4;
     const unsigned pair = blockIdx.x / blocks_per_pair;
     const unsigned blk = blockIdx.x - pair * blocks_per_pair;
-    const long long nvec = a.n / W;
+    const long long nvec = a.n / 4;
     const char *src = static_cast<const char *>(a.src[pair]);
     float *dst = a.dst[pair];
-    const long long stride = static_cast<long long>(blocks_per_pair) * blockDim.x;
-    for (long long vi = static_cast<long long>(blk) * blockDim.x + threadIdx.x; vi < nvec;
-         vi += stride) {
-        const long long e = a.e0 + vi * W;
-        const u32x4 g = ld_u4<true>(src + e * (BF16 ? 2 : 4));
-        if (BF16) {
-            st_f4<true>(dst + e, widen_lo(g, 0));
-            st_f4<true>(dst + e + 4, widen_lo(g, 1));
-        } else {
-            st_f4<true>(dst + e, __builtin_bit_cast(f32x4, g));
+    // a workgroup copies V * blockDim consecutive lane-vectors per iteration: all loads
+    // first, then the stores
+    const long long tile = static_cast<long long>(blockDim.x) * V;
+    for (long long base = static_cast<long long>(blk) * tile; base < nvec;
+         base += static_cast<long long>(blocks_per_pair) * tile) {
+        f32x4 x[V];
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const long long vi = base + static_cast<long long>(k) * blockDim.x + threadIdx.x;
+            if (vi < nvec) {
+                const long long e = a.e0 + vi * 4;
+                if (BF16) {
+                    const u32x2 g = __builtin_nontemporal_load(
+                        reinterpret_cast<const u32x2 *>(src + e * 2));
+                    x[k].x = __uint_as_float(g.x << 16);
+                    x[k].y = __uint_as_float(g.x & 0xffff0000u);
+                    x[k].z = __uint_as_float(g.y << 16);
+                    x[k].w = __uint_as_float(g.y & 0xffff0000u);
+                } else {
+                    x[k] = ld_f4<true>(reinterpret_cast<const float *>(src + e * 4));
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const long long vi = base + static_cast<long long>(k) * blockDim.x + threadIdx.x;
+            if (vi < nvec) st_f4<true>(dst + a.e0 + vi * 4, x[k]);
         }
     }
-    const long long rem = a.n - nvec * W;
+    const long long rem = a.n - nvec * 4;
     if (blk == 0 && static_cast<long long>(threadIdx.x) < rem) {
-        const long long i = a.e0 + nvec * W + threadIdx.x;
+        const long long i = a.e0 + nvec * 4 + threadIdx.x;
         dst[i] = load_grad_scalar<BF16>(src, i);
     }
 }
@@ -548,6 +624,13 @@ __global__ __launch_bounds__(256) void read_kernel(const f32x4 *src, long long n
 // HBM throughput falls again).
 constexpr int kLdsPerCu = 160 * 1024;
 
+// A grid must hold fewer than 2^32 threads in total; a launch beyond that is not refused
+// by the runtime, its thread count wraps.  Every launcher stays at or below 2^31.
+constexpr long long kMaxGridThreads = 1ll << 31;
+
+// Parameters and momentum above this size are streamed past the caches (see slot_vectors).
+constexpr long long kStateCacheBytes = 256ll << 20;
+
 // Resident workgroups per CU when the caller leaves the choice to the library: measured
 // optima of the rank-chunk kernel with 64-thread workgroups for 1, 2 and 4 chunks of 8.
 int auto_blocks_per_cu(int P, int block, bool bf16)
@@ -558,23 +641,28 @@ int auto_blocks_per_cu(int P, int block, bool bf16)
     return b < 1 ? 1 : b;
 }
 
-template <typename K, typename A>
+template <typename K, typename A, typename... Extra>
 hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, unsigned grid,
-                         hipStream_t st)
+                         hipStream_t st, Extra... extra)
 {
     unsigned lds = 0;
     if (bpc > 0) {
         lds = static_cast<unsigned>(kLdsPerCu / bpc) & ~2047u;
-        static bool raised = false;   // one flag per kernel instantiation
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+        // Kernels of one signature share this function, so the flag is kept per kernel
+        // address (a handful of entries; a context is not used from several threads, the
+        // mutex covers several contexts).
+        static std::mutex mu;
+        static std::set<const void *> raised;
+        const void *fn = reinterpret_cast<const void *>(kernel);
+        std::lock_guard<std::mutex> lock(mu);
+        if (!raised.count(fn)) {
+            hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                kLdsPerCu);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised.insert(fn);
         }
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(cfg.block), lds, st, a);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(cfg.block), lds, st, a, extra...);
     return hipGetLastError();
 }
 
@@ -592,27 +680,29 @@ hipError_t launch_capped(K kernel, const RoundArgs &a, const Launch &cfg, unsign
 void build_slots(const RoundArgs &a, SlotArgs &s)
 {
     s.n_slots = 0;
-    s.kind0[0] = s.kind0[1] = s.kind1[0] = s.kind1[1] = 0;
-    auto push = [&s](const float *src, float *dst, int kind) {
+    s.kind0[0] = s.kind0[1] = s.kind1[0] = s.kind1[1] = s.bf[0] = s.bf[1] = 0;
+    const bool bf16 = a.elem_bytes == 2;
+    auto push = [&s](const void *src, float *dst, int kind, bool is_bf) {
         const int k = s.n_slots++;
         s.src[k] = src;
         s.dst[k] = dst;
         if (kind & 1) s.kind0[k >> 6] |= 1ull << (k & 63);
         if (kind & 2) s.kind1[k >> 6] |= 1ull << (k & 63);
+        if (is_bf) s.bf[k >> 6] |= 1ull << (k & 63);
     };
     for (int p = 0; p < a.P; ++p) {
         const bool on_time = (a.active >> p) & 1ull, has_stale = (a.valid >> p) & 1ull;
-        const float *g = static_cast<const float *>(a.g[p]);
+        const void *g = a.g[p];
         if (on_time) {
             if (has_stale) {
-                push(a.r[p], nullptr, kHold);
-                push(g, nullptr, kPair);
+                push(a.r[p], nullptr, kHold, false);
+                push(g, nullptr, kPair, bf16);
             } else {
-                push(g, nullptr, kAdd);
+                push(g, nullptr, kAdd, bf16);
             }
         } else {
-            if (has_stale) push(a.r[p], nullptr, kAdd);
-            if ((a.store >> p) & 1ull) push(g, a.r[p], kStore);
+            if (has_stale) push(a.r[p], nullptr, kAdd, false);
+            if ((a.store >> p) & 1ull) push(g, a.r[p], kStore, bf16);
         }
     }
     s.w = a.w;
@@ -626,37 +716,46 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
 }
 
 // Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of
-// late gradients in the same pass few wavefronts are best once there are many streams;
-// a pass that only reads (apart from w and v) likes more.
-int auto_waves_for_slots(int n_slots, bool has_stores)
+// late gradients in the same pass few wavefronts are best once there are many streams
+// (bf16 gradients, whose loads carry half the bytes, like a few more); a pass that only
+// reads (apart from w and v) likes more.
+int auto_waves_for_slots(int n_slots, bool has_stores, bool bf16)
 {
-    if (has_stores) return n_slots <= 16 ? 8 : 5;   // one chunk of 16 or several
+    if (has_stores) return n_slots <= 16 ? 8 : bf16 ? 7 : 5;   // one chunk of 16 or several
     return n_slots <= 20 ? 10 : 6;
 }
 
-template <bool FAST>
+template <bool BF16, bool FAST>
 hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
 {
     SlotArgs s;
     build_slots(a, s);
     int bpc = cfg.blocks_per_cu;
     if (bpc == 0) {
-        bpc = (auto_waves_for_slots(s.n_slots, a.store != 0) * 64 + cfg.block - 1) / cfg.block;
+        bpc = (auto_waves_for_slots(s.n_slots, a.store != 0, BF16) * 64 + cfg.block - 1) / cfg.block;
         if (bpc < 1) bpc = 1;
     }
     // one vector per lane, the grid covers the run ("unroll" and "max_blocks" do not apply);
     // always nontemporal (the A/B against plain loads and stores lives in the rank-chunk
     // kernel)
-    const long long nvec = s.n / 4;
+    const long long nvec = slot_nvec<BF16>(s.n);
     long long g = (nvec + cfg.block - 1) / cfg.block;
     if (g < 1) g = 1;
-    if (g > 0x7fffffffLL) return hipErrorInvalidValue;
+    // this kernel does not stride: a run beyond the thread limit of a grid (more than
+    // 2^33 elements) is refused
+    if (g * cfg.block > kMaxGridThreads) return hipErrorInvalidValue;
     const unsigned grid = static_cast<unsigned>(g);
     int ch = cfg.chunk;
     if (ch == 0) ch = 16;
-    switch (ch) {
-    case 8: return launch_capped(slot_kernel<FAST, true, 8>, s, bpc, cfg, grid, st);
-    case 16: return launch_capped(slot_kernel<FAST, true, 16>, s, bpc, cfg, grid, st);
+    // w, v (and recv) of a run that cannot stay in the 256 MiB last-level cache until the
+    // next round are streamed; smaller ones are left to the cache
+    const long long state_bytes = s.n * 4 * ((s.w ? 2 : 0) + (s.recv ? 1 : 0));
+    const bool nts = cfg.nt_state < 0 ? state_bytes > kStateCacheBytes : cfg.nt_state != 0;
+    switch (ch * 2 + (nts ? 1 : 0)) {
+    case 16: return launch_capped(slot_kernel<BF16, FAST, true, false, 8>, s, bpc, cfg, grid, st);
+    case 17: return launch_capped(slot_kernel<BF16, FAST, true, true, 8>, s, bpc, cfg, grid, st);
+    case 32: return launch_capped(slot_kernel<BF16, FAST, true, false, 16>, s, bpc, cfg, grid, st);
+    case 33: return launch_capped(slot_kernel<BF16, FAST, true, true, 16>, s, bpc, cfg, grid, st);
     default: return hipErrorInvalidValue;   // more streams per chunk exceed the scalar registers
     }
 }
@@ -704,7 +803,8 @@ unsigned grid_for(long long nvec, long long per_block, int max_blocks)
     long long g = (nvec + per_block - 1) / per_block;
     if (g < 1) g = 1;
     if (max_blocks > 0 && g > max_blocks) g = max_blocks;
-    if (g > 0x7fffffffLL) g = 0x7fffffffLL;   // the kernels stride, so a cap is safe
+    // the kernels stride, so a cap is safe; workgroups have at most 256 threads
+    if (g > kMaxGridThreads / 256) g = kMaxGridThreads / 256;
     return static_cast<unsigned>(g);
 }
 
@@ -717,30 +817,52 @@ hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &
     const long long nvec = a.n / (bf16 ? 8 : 4);
     const unsigned grid = grid_for(nvec, static_cast<long long>(cfg.block) * cfg.unroll,
                                    cfg.max_blocks);
+    if (cfg.compact) {
+        if (bf16)
+            return fast ? launch_slots<true, true>(a, cfg, stream)
+                        : launch_slots<true, false>(a, cfg, stream);
+        return fast ? launch_slots<false, true>(a, cfg, stream)
+                    : launch_slots<false, false>(a, cfg, stream);
+    }
     if (bf16)
         return fast ? launch_round_nt<true, true>(a, cfg, grid, stream)
                     : launch_round_nt<true, false>(a, cfg, grid, stream);
-    if (cfg.compact)
-        return fast ? launch_slots<true>(a, cfg, stream) : launch_slots<false>(a, cfg, stream);
     return fast ? launch_round_nt<false, true>(a, cfg, grid, stream)
                 : launch_round_nt<false, false>(a, cfg, grid, stream);
 }
 
-hipError_t launch_carry(const CarryArgs &a, bool bf16, hipStream_t stream)
+template <bool BF16, int V>
+hipError_t launch_carry_v(const CarryArgs &a, const Launch &cfg, hipStream_t stream)
+{
+    const long long nvec = a.n / 4;
+    const long long tile = static_cast<long long>(cfg.carry_block) * V;
+    long long bpp = (nvec + tile - 1) / tile;
+    if (bpp < 1) bpp = 1;
+    // a grid may hold fewer than 2^32 threads in all; beyond that the kernel strides
+    const long long cap = kMaxGridThreads / cfg.carry_block / a.count;
+    if (bpp > cap) bpp = cap;
+    const unsigned grid = static_cast<unsigned>(bpp) * static_cast<unsigned>(a.count);
+    Launch l = cfg;
+    l.block = cfg.carry_block;
+    return launch_capped(carry_kernel<BF16, V>, a, cfg.carry_blocks_per_cu, l, grid, stream,
+                         static_cast<unsigned>(bpp));
+}
+
+template <bool BF16>
+hipError_t launch_carry_t(const CarryArgs &a, const Launch &cfg, hipStream_t stream)
+{
+    switch (cfg.carry_vec) {
+    case 1: return launch_carry_v<BF16, 1>(a, cfg, stream);
+    case 2: return launch_carry_v<BF16, 2>(a, cfg, stream);
+    case 4: return launch_carry_v<BF16, 4>(a, cfg, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream)
 {
     if (a.n <= 0 || a.count <= 0) return hipSuccess;
-    const long long nvec = a.n / (bf16 ? 8 : 4);
-    long long bpp = (nvec + 255) / 256;
-    if (bpp < 1) bpp = 1;
-    if (bpp > 0x7fffffffLL / a.count) bpp = 0x7fffffffLL / a.count;   // the kernel strides
-    const unsigned grid = static_cast<unsigned>(bpp) * static_cast<unsigned>(a.count);
-    if (bf16)
-        hipLaunchKernelGGL(carry_kernel<true>, dim3(grid), dim3(256), 0, stream, a,
-                           static_cast<unsigned>(bpp));
-    else
-        hipLaunchKernelGGL(carry_kernel<false>, dim3(grid), dim3(256), 0, stream, a,
-                           static_cast<unsigned>(bpp));
-    return hipGetLastError();
+    return bf16 ? launch_carry_t<true>(a, cfg, stream) : launch_carry_t<false>(a, cfg, stream);
 }
 
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream)

@@ -52,9 +52,13 @@ def sample_indices(cfg, n_random=30000, seed=0):
     return idx[inside].astype(np.int64)
 
 
-@pytest.mark.parametrize("k,steps,order", [(2, 8, 0), (2, 4, 1), (3, 5, 0), (4, 3, 0), (5, 3, 0),
-                                           (5, 2, 1)])
-def test_full_size_sampled(eb, k, steps, order):
+# The last case forces the split form (reduction kernel + send-buffer copy kernel) on the
+# largest configuration: 15 copies of 1.56e9 elements in one launch, which is where a grid
+# would exceed the device's limit of 2^32 threads if the launcher did not cap it.
+@pytest.mark.parametrize("k,steps,order,launch", [
+    (2, 8, 0, {}), (2, 4, 1, {}), (3, 5, 0, {}), (4, 3, 0, {}), (5, 3, 0, {}), (5, 2, 1, {}),
+    (5, 2, 0, {"split": 2})])
+def test_full_size_sampled(eb, k, steps, order, launch):
     cfg = shapes.config(k)
     bt = cfg.buckets
     dev = torch.device("cuda:0")
@@ -66,6 +70,8 @@ def test_full_size_sampled(eb, k, steps, order):
 
     ctx = eb.Context(cfg.P, bt.offset, bt.numel, eb.BF16 if cfg.grad_dtype == "bf16" else eb.F32,
                      order)
+    for key, val in launch.items():
+        ctx.eager_set_launch(key, val)
     G = [torch.empty(n, dtype=gdt, device=dev) for _ in range(cfg.P)]
     R = [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(cfg.P)]
     w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)

@@ -134,18 +134,28 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
     cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 3), 40000)
     bt = cfg.buckets
     ref = None
-    for block, unroll, maxb, nt, chunk, bpc, split, compact in [
-            (256, 1, 0, 1, 0, 0, 1, 1), (64, 2, 0, 1, 4, 4, 2, 0), (128, 1, 3, 0, 16, 2, 1, 1),
-            (256, 1, 0, 1, 16, 1, 2, 1), (256, 2, 7, 0, 8, 3, 0, 1), (64, 2, 0, 1, 8, -1, 2, 1),
-            (64, 1, 2, 1, 32 if dtype == "f32" else 16, 5, 2, 0)]:
+    shapes_ = [
+        dict(block=256, unroll=1, max_blocks=0, nontemporal=1, chunk=0, blocks_per_cu=0, split=1,
+             compact=1),
+        dict(block=64, unroll=2, max_blocks=0, nontemporal=1, chunk=4, blocks_per_cu=4, split=2,
+             compact=0),
+        dict(block=128, unroll=1, max_blocks=3, nontemporal=0, chunk=16, blocks_per_cu=2, split=1,
+             compact=1, nt_state=0),
+        dict(block=256, unroll=1, max_blocks=0, nontemporal=1, chunk=16, blocks_per_cu=1, split=2,
+             compact=1, nt_state=1, carry_block=256, carry_vec=4, carry_blocks_per_cu=2),
+        dict(block=256, unroll=2, max_blocks=7, nontemporal=0, chunk=8, blocks_per_cu=3, split=0,
+             compact=1, carry_block=128, carry_vec=2),
+        dict(block=64, unroll=2, max_blocks=0, nontemporal=1, chunk=8, blocks_per_cu=-1, split=2,
+             compact=1, carry_vec=2, carry_blocks_per_cu=32),
+        dict(block=64, unroll=1, max_blocks=2, nontemporal=1, chunk=32 if dtype == "f32" else 16,
+             blocks_per_cu=5, split=2, compact=0, carry_block=64, carry_vec=4)]
+    for launch in shapes_:
         pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, seed=4)
-        for key, val in (("block", block), ("unroll", unroll), ("max_blocks", maxb),
-                         ("nontemporal", nt), ("chunk", chunk), ("blocks_per_cu", bpc),
-                         ("split", split), ("compact", compact)):
+        for key, val in launch.items():
             pair.ctx.eager_set_launch(key, val)
         for t in range(3):
             pair.round(plan_for(eb, cfg, t), pair.fresh_grads(t))
-        pair.compare(exact=True, what=f"launch {block}/{unroll}/{maxb}/{nt}/{chunk}/{bpc}/{split}/{compact}")
+        pair.compare(exact=True, what=f"launch {launch}")
         torch.cuda.synchronize()
         if ref is None:
             ref = pair.w.clone()
