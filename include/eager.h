@@ -161,7 +161,8 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
  * combination the library has no kernel for makes the next round fail with EDEVICE.
  *   "compact"    1 (default) = only the streams a round needs are listed and read (one
  *                group of 4 elements per lane, grid covers the range; "unroll",
- *                "max_blocks" and "nontemporal" do not apply, "chunk" is 8 or 16);
+ *                "max_blocks" and "nontemporal" do not apply, "chunk" is 8, 16 (default)
+ *                or 32);
  *                0 = fixed rank chunks with cached stand-in loads
  *   "split"      0 = chosen per round (default: fp32 gradients on the compact path are split
  *                when 8 or more processes are late, or when somebody is late and the fused

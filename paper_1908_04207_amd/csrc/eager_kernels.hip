@@ -324,12 +324,17 @@ __device__ __forceinline__ f32x4 slot_value(u32x4 raw, bool is_bf, bool odd)
     return is_bf ? wide : plain;
 }
 
+__device__ __forceinline__ f32x4 masked(f32x4 x, unsigned m)
+{
+    return __builtin_bit_cast(f32x4, __builtin_bit_cast(u32x4, x) & m);
+}
+
 template <bool BF16, bool FAST, bool NT, int U, int C>
 __device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const LaneVec (&lv)[U],
                                            f32x4 (&s)[U][2], f32x4 (&hold)[U])
 {
-    // a chunk starts at a multiple of 8 or 16 and holds at most 16 slots: its bits never
-    // straddle a mask word
+    // a chunk starts at a multiple of its size (8, 16 or 32): its bits never straddle a
+    // mask word
     const unsigned long long b0 = a.kind0[k0 >> 6] >> (k0 & 63);
     const unsigned long long b1 = a.kind1[k0 >> 6] >> (k0 & 63);
     const unsigned long long bf = BF16 ? a.bf[k0 >> 6] >> (k0 & 63) : 0ull;
@@ -342,30 +347,40 @@ __device__ __forceinline__ void slot_chunk(KSlotArgs &a, int k0, const LaneVec (
         for (int u = 0; u < U; ++u)
             raw[u][j] = ld_u4<NT>(sp + (is_bf ? lv[u].off_bf : lv[u].e * 4));
     }
-    // Every loaded value is used unconditionally (selects on scalar conditions, not
-    // branches): if a path existed on which a load is never consumed, the compiler would
-    // have to drain all memory operations before its registers could be reused.
+    // Every loaded value is used unconditionally and the action of a slot is applied with
+    // bit masks built from scalar conditions, never with a branch: if a path existed on
+    // which a load is not consumed, the compiler would have to drain all memory operations
+    // before its registers could be reused.
+    //   fixed order:  c = x + (prev & pair) ;  s = s + (c & adds)
+    // where prev is the value of the slot before (a HOLD is always directly followed by its
+    // PAIR; `hold` carries the last value of the previous chunk), pair = all ones for a PAIR
+    // slot, adds = all ones for ADD and PAIR.  A masked-out term is +0.0f, and adding +0.0f
+    // changes nothing here: s starts at +0.0f and a sum of two floats is -0.0f only if both
+    // are, so s is never -0.0f; and c = x + 0.0f differs from x only for x = -0.0f, which
+    // adds the same as +0.0f to an s that is not -0.0f.
     f32x4 x[U][C];
 #pragma unroll
     for (int j = 0; j < C; ++j) {
-        const bool lo = (b0 >> j) & 1ull, hi = (b1 >> j) & 1ull;
-        const bool is_add = !lo && !hi, is_hold = lo && !hi, is_pair = !lo && hi;
+        const unsigned lo = static_cast<unsigned>(b0 >> j) & 1u;
+        const unsigned hi = static_cast<unsigned>(b1 >> j) & 1u;
+        const unsigned m_pair = 0u - (hi & ~lo & 1u);          // PAIR
+        const unsigned m_adds = 0u - (~lo & 1u);               // ADD or PAIR
+        const unsigned m_sum = ~(0u - (lo & hi));              // everything but STORE
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             x[u][j] = slot_value<BF16>(raw[u][j], (bf >> j) & 1ull, lv[u].odd);
             if (FAST) {
                 // any order: two interleaved partial sums
-                const f32x4 t = s[u][j & 1] + x[u][j];
-                s[u][j & 1] = (lo && hi) ? s[u][j & 1] : t;
+                s[u][j & 1] = s[u][j & 1] + masked(x[u][j], m_sum);
             } else {
-                const f32x4 pair = hold[u] + x[u][j];
-                const f32x4 c = is_pair ? pair : x[u][j];
-                const f32x4 t = s[u][0] + c;
-                s[u][0] = (is_add || is_pair) ? t : s[u][0];
-                hold[u] = is_hold ? x[u][j] : hold[u];
+                const f32x4 prev = j == 0 ? hold[u] : x[u][j - 1];
+                const f32x4 c = x[u][j] + masked(prev, m_pair);
+                s[u][0] = s[u][0] + masked(c, m_adds);
             }
         }
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) hold[u] = x[u][C - 1];
     // Stores stay behind the adds: moved ahead of them (the compiler likes to sink the add
     // chain below the store branches), the in-order memory counter would make every add
     // wait for the acknowledgement of a store instead of for its load.  The empty
@@ -722,7 +737,7 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
 int auto_waves_for_slots(int n_slots, bool has_stores, bool bf16)
 {
     if (has_stores) return n_slots <= 16 ? 8 : bf16 ? 7 : 5;   // one chunk of 16 or several
-    return n_slots <= 20 ? 10 : 6;
+    return n_slots <= 20 ? 10 : 5;
 }
 
 template <bool BF16, bool FAST>
@@ -756,6 +771,8 @@ hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
     case 17: return launch_capped(slot_kernel<BF16, FAST, true, true, 8>, s, bpc, cfg, grid, st);
     case 32: return launch_capped(slot_kernel<BF16, FAST, true, false, 16>, s, bpc, cfg, grid, st);
     case 33: return launch_capped(slot_kernel<BF16, FAST, true, true, 16>, s, bpc, cfg, grid, st);
+    case 64: return launch_capped(slot_kernel<BF16, FAST, true, false, 32>, s, bpc, cfg, grid, st);
+    case 65: return launch_capped(slot_kernel<BF16, FAST, true, true, 32>, s, bpc, cfg, grid, st);
     default: return hipErrorInvalidValue;   // more streams per chunk exceed the scalar registers
     }
 }
