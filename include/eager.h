@@ -41,7 +41,7 @@ extern "C" {
 
 typedef struct eager_ctx eager_ctx;   /* opaque: bucket table, send-buffer validity, last error */
 
-typedef enum { EAGER_SOLO = 0, EAGER_MAJORITY = 1 } eager_mode;
+typedef enum { EAGER_SOLO = 0, EAGER_MAJORITY = 1, EAGER_QUORUM = 2 } eager_mode;
 typedef enum { EAGER_F32 = 0, EAGER_BF16 = 1 } eager_dtype;          /* type of G only */
 typedef enum { EAGER_ORDER_FIXED = 0, EAGER_ORDER_FAST = 1 } eager_order;
 
@@ -118,6 +118,18 @@ int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t
                              eager_plan *out);
 
 /*
+ * The spectrum between solo, majority and a full allreduce that the paper's conclusions
+ * (Section 9) propose: the round triggers when `quorum` (1..P) processes have reached the
+ * collective.  The initiator is the quorum-th arrival (ties: lowest rank first); active =
+ * every process that arrived no later than the initiator plus window_ms.  quorum = 1 gives
+ * the solo participation set, quorum = P a full allreduce.  out->mode is EAGER_QUORUM.
+ * Host only, pure.  Errors: EINVAL (NULL, P outside 1..64, quorum outside 1..P, NaN time,
+ * negative window).
+ */
+int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step,
+                      double window_ms, eager_plan *out);
+
+/*
  * One round of the partial allreduce over buckets [b0, b1) (Section 5; Algorithm 2
  * line 6), optionally fused with the update rule (lines 7-8).
  *   plan    host; produced by eager_plan_participation or built by the caller
@@ -131,8 +143,8 @@ int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t
  *   opt     host or NULL.  Non-NULL: w and v are updated in the same pass.  NULL:
  *           only recv is produced (then recv must not be NULL)
  * On success the validity of every bucket in the range becomes ~mask.
- * The two entry points run the same kernels and differ in what they accept:
- * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY.
+ * The three entry points run the same kernels and differ in what they accept:
+ * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY, _quorum EAGER_QUORUM.
  * Errors: EINVAL (NULL, alignment, b0 >= b1, range), ESTATE (mode or P mismatch,
  * initiator not in mask, nap != popcount(mask), mask beyond P bits, bucket already
  * stepped with this plan->step), EDEVICE.  Non-finite gradients are not an error; they
@@ -144,6 +156,9 @@ int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0,
 int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                      const void *const *grads, float *const *resid,
                                      float *recv, const eager_opt *opt, void *stream);
+int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                   const void *const *grads, float *const *resid,
+                                   float *recv, const eager_opt *opt, void *stream);
 
 /* The update rule alone (Algorithm 2, lines 7-8) on buckets [b0, b1): reads u from
  * `update` (device fp32 arena, e.g. a receive buffer), updates opt->params/momentum.

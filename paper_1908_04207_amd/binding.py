@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libeager.so")
 
-SOLO, MAJORITY = 0, 1
+SOLO, MAJORITY, QUORUM = 0, 1, 2
 F32, BF16 = 0, 1
 ORDER_FIXED, ORDER_FAST = 0, 1
 OK, EINVAL, ESHAPE, ESTATE, EDEVICE, ENOMEM = range(6)
@@ -24,7 +24,8 @@ MAX_P = 64
 EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
-    "eager_partial_allreduce_majority", "eager_sgd_step", "eager_get_valid",
+    "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
+    "eager_sgd_step", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
 )
 
@@ -55,6 +56,11 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_1908_04207_amd.build` "
             "(hipcc, gfx950); there is no fallback path")
+    # The library and PyTorch must share ONE HIP runtime (streams and device pointers cross
+    # between them).  PyTorch ships its own copy under the same SONAME: loaded first, it
+    # also serves this library; loaded second, the process would hold two runtimes and the
+    # second one finds no device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_uint64
     lib.eager_create.argtypes = [ctypes.POINTER(vp), i32, i32, ctypes.POINTER(i64),
@@ -67,7 +73,10 @@ def _load() -> ctypes.CDLL:
     lib.eager_plan_participation.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), u64, u64,
                                              ctypes.c_double, ctypes.c_uint32,
                                              ctypes.POINTER(Plan)]
-    for f in (lib.eager_partial_allreduce_solo, lib.eager_partial_allreduce_majority):
+    lib.eager_plan_quorum.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i32, u64,
+                                      ctypes.c_double, ctypes.POINTER(Plan)]
+    for f in (lib.eager_partial_allreduce_solo, lib.eager_partial_allreduce_majority,
+              lib.eager_partial_allreduce_quorum):
         f.argtypes = [vp, ctypes.POINTER(Plan), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                       vp, ctypes.POINTER(Opt), vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
@@ -112,6 +121,17 @@ def eager_plan_participation(mode: int, arrival_ms: Sequence[float], seed: int, 
                                       ctypes.byref(plan))
     if st != OK:
         raise EagerError(st, f"eager_plan_participation: {status_string(st)}")
+    return plan
+
+
+def eager_plan_quorum(arrival_ms: Sequence[float], quorum: int, step: int,
+                      window_ms: float = 0.0) -> Plan:
+    P = len(arrival_ms)
+    arr = (ctypes.c_double * max(P, 1))(*arrival_ms)
+    plan = Plan()
+    st = lib.eager_plan_quorum(P, arr, quorum, step, window_ms, ctypes.byref(plan))
+    if st != OK:
+        raise EagerError(st, f"eager_plan_quorum: {status_string(st)}")
     return plan
 
 
@@ -175,10 +195,16 @@ class Context:
         self._allreduce(lib.eager_partial_allreduce_majority, "eager_partial_allreduce_majority",
                         plan, grads, resid, recv, opt, b0, b1, stream)
 
+    def eager_partial_allreduce_quorum(self, plan: Plan, grads, resid, recv=None, opt=None,
+                                       b0: int = 0, b1: Optional[int] = None, stream=None):
+        self._allreduce(lib.eager_partial_allreduce_quorum, "eager_partial_allreduce_quorum",
+                        plan, grads, resid, recv, opt, b0, b1, stream)
+
     def eager_partial_allreduce(self, plan: Plan, *a, **kw):
         """Dispatch on plan.mode to the entry point of that name."""
-        fn = (self.eager_partial_allreduce_solo if plan.mode == SOLO
-              else self.eager_partial_allreduce_majority)
+        fn = {SOLO: self.eager_partial_allreduce_solo,
+              MAJORITY: self.eager_partial_allreduce_majority,
+              QUORUM: self.eager_partial_allreduce_quorum}[plan.mode]
         fn(plan, *a, **kw)
 
     def eager_sgd_step(self, update, opt, b0: int = 0, b1: Optional[int] = None, stream=None):

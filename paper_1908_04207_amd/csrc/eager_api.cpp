@@ -295,6 +295,35 @@ int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t
     return EAGER_OK;
 }
 
+int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step,
+                      double window_ms, eager_plan *out)
+{
+    if (!arrival_ms || !out) return EAGER_EINVAL;
+    if (P < 1 || P > EAGER_MAX_P || quorum < 1 || quorum > P) return EAGER_EINVAL;
+    if (!(window_ms >= 0.0)) return EAGER_EINVAL;
+    for (int p = 0; p < P; ++p)
+        if (std::isnan(arrival_ms[p])) return EAGER_EINVAL;
+    // ranks in order of arrival, equal times by rank (stable insertion sort, P <= 64)
+    int order[EAGER_MAX_P];
+    for (int i = 0; i < P; ++i) {
+        int j = i - 1;
+        while (j >= 0 && arrival_ms[order[j]] > arrival_ms[i]) { order[j + 1] = order[j]; --j; }
+        order[j + 1] = i;
+    }
+    const int init = order[quorum - 1];
+    const double threshold = arrival_ms[init] + window_ms;
+    uint64_t mask = 0;
+    for (int p = 0; p < P; ++p)
+        if (arrival_ms[p] <= threshold) mask |= 1ull << p;
+    out->mode = EAGER_QUORUM;
+    out->P = P;
+    out->step = step;
+    out->mask = mask;
+    out->initiator = init;
+    out->nap = popcount64(mask);
+    return EAGER_OK;
+}
+
 int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                  const void *const *grads, float *const *resid, float *recv,
                                  const eager_opt *opt, void *stream)
@@ -307,6 +336,13 @@ int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int
                                      const eager_opt *opt, void *stream)
 {
     return partial_allreduce(ctx, EAGER_MAJORITY, plan, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
+                                   const void *const *grads, float *const *resid, float *recv,
+                                   const eager_opt *opt, void *stream)
+{
+    return partial_allreduce(ctx, EAGER_QUORUM, plan, b0, b1, grads, resid, recv, opt, stream);
 }
 
 int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,

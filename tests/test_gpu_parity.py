@@ -81,6 +81,25 @@ def test_rank_counts_and_random_masks(eb, P, dtype):
         pair.compare(exact=True, check_recv=True, what=f"P={P} {dtype} t={t} mask={mask:#x}")
 
 
+def test_quorum_rounds(eb):
+    """k-of-P participation through eager_plan_quorum / eager_partial_allreduce_quorum, k
+    sweeping from solo to full, on the LSTM layout; bitwise."""
+    from oracle import eager_oracle as eo
+    from workloads import times as wt
+    cfg = shapes.scaled(shapes.config(3), 30011)
+    bt = cfg.buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, "f32", eb.ORDER_FIXED, seed=11)
+    for t, k in enumerate([1, 4, 8, 12, 16, 2, 16]):
+        arr = wt.compute_times(cfg.times, cfg.P, cfg.seed, t)
+        plan = eb.eager_plan_quorum(arr, k, t)
+        ref = eo.plan_participation(eo.QUORUM, cfg.P, arr, 0, t, quorum=k)
+        assert (plan.mask, plan.initiator, plan.nap) == (ref.mask, ref.initiator, ref.nap)
+        assert plan.nap >= k
+        pair.round(plan, pair.fresh_grads(t), want_recv=True)
+        pair.compare(exact=True, check_recv=True, what=f"quorum {k} of {cfg.P}, t={t}")
+    assert all(pair.ctx.eager_get_valid(b) == 0 for b in range(bt.n_buckets))
+
+
 def test_bucket_ranges_with_different_histories(eb):
     """Buckets stepped by separate calls with different masks end up in different
     send-buffer states; a later whole-range call must split into runs."""

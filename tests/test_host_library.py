@@ -52,6 +52,33 @@ def test_plan_matches_oracle_random_with_ties_window_and_strict_quorum():
                 assert (a.mask, a.initiator, a.nap) == (b.mask, b.initiator, b.nap)
 
 
+def test_quorum_plan_matches_oracle_and_spans_solo_to_full():
+    """k-of-P participation (Section 9): same sets as the oracle; k = 1 is the solo set,
+    k = P everybody; the set grows with k."""
+    rng = np.random.default_rng(1)
+    for it in range(500):
+        P = int(rng.integers(1, 65))
+        t = rng.integers(0, 6, P).astype(float).tolist() if it % 2 else rng.random(P).tolist()
+        window = float(rng.choice([0.0, 0.5]))
+        prev = 0
+        for k in range(1, P + 1):
+            a = eb.eager_plan_quorum(t, k, it, window)
+            b = eo.plan_participation(eo.QUORUM, P, t, 0, it, window, quorum=k)
+            assert (a.mode, a.mask, a.initiator, a.nap) == (eb.QUORUM, b.mask, b.initiator, b.nap)
+            assert a.nap >= k and a.mask & prev == prev
+            prev = a.mask
+        assert eb.eager_plan_quorum(t, 1, it, window).mask == \
+            eb.eager_plan_participation(eb.SOLO, t, 0, it, window).mask
+        assert eb.eager_plan_quorum(t, P, it).mask == (1 << P) - 1
+    for bad in (lambda: eb.eager_plan_quorum([1.0, 2.0], 0, 0),
+                lambda: eb.eager_plan_quorum([1.0, 2.0], 3, 0),
+                lambda: eb.eager_plan_quorum([1.0, float("nan")], 1, 0),
+                lambda: eb.eager_plan_quorum([1.0], 1, 0, window_ms=-1.0)):
+        with pytest.raises(eb.EagerError) as e:
+            bad()
+        assert e.value.status == eb.EINVAL
+
+
 def test_plan_rejects_bad_arguments():
     for bad in (lambda: eb.eager_plan_participation(7, [1.0], 0, 0),
                 lambda: eb.eager_plan_participation(eb.SOLO, [], 0, 0),
@@ -97,6 +124,7 @@ def test_allreduce_validation_happens_before_any_launch():
         assert e.value.status == status, str(e.value)
 
     expect(eb.ESTATE, eb.make_plan(eb.MAJORITY, P, 0, 0b0011))          # wrong entry point
+    expect(eb.ESTATE, eb.make_plan(eb.QUORUM, P, 0, 0b0011))
     expect(eb.ESTATE, eb.make_plan(eb.SOLO, 5, 0, 0b0011))              # P mismatch
     expect(eb.ESTATE, eb.make_plan(eb.SOLO, P, 0, 0b10011))             # mask beyond P
     expect(eb.ESTATE, eb.make_plan(eb.SOLO, P, 0, 0b0011, initiator=3))  # initiator not active
