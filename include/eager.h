@@ -166,6 +166,17 @@ int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b
 int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update,
                    const eager_opt *opt, void *stream);
 
+/*
+ * Variants of the update rule U (the paper leaves U generic, Algorithm 2 line 7).  They apply
+ * to every later fused round and eager_sgd_step of this context:
+ *     g  = u + weight_decay * w        (skipped when weight_decay == 0)
+ *     v' = mu * v + g
+ *     w' = w - lr * (nesterov ? g + mu * v' : v')
+ * each line one fused multiply-add in fixed-order mode.  The default (0, 0) is heavy-ball
+ * momentum SGD.  Errors: EINVAL (negative or non-finite weight_decay, nesterov not 0/1).
+ */
+int eager_set_update_rule(eager_ctx *ctx, float weight_decay, int nesterov);
+
 /* Send-buffer validity of one bucket (bit p: R_p holds an undelivered gradient);
  * together with w, v, R and the round index this is all the state a resume needs. */
 int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask);

@@ -21,7 +21,10 @@
  *
  * Readings where the paper is silent (they are conventions of this repository):
  *   - U is heavy-ball momentum SGD, v <- mu*v + u, w <- w - lr*v, each as one fused
- *     multiply-add (single rounding); no Nesterov, no weight decay.
+ *     multiply-add (single rounding).  The paper leaves U generic (Algorithm 2, line 7);
+ *     two common variants are available and off by default: weight decay (g = u + wd*w
+ *     enters the rule in place of u) and Nesterov momentum (the step is g + mu*v' instead
+ *     of v'), each again one fused multiply-add.
  *   - fp32 throughout, round-to-nearest-even; the P contributions are added in
  *     ascending rank order starting from +0.0f; 1/P is computed once in fp32 and
  *     multiplied.  This fixed order is what makes a bit-exact comparison possible.
@@ -45,6 +48,21 @@ static inline float widen_bf16(uint16_t h)
     return f;
 }
 
+/* The update rule U on one element (Algorithm 2, lines 7-8), with the optional variants. */
+static inline void update_rule(float u, float *w, float *v, float lr, float mu, float wd,
+                               int nesterov)
+{
+    float g = u, vn, step;
+    if (wd != 0.0f)
+        g = fmaf(wd, *w, u);
+    vn = fmaf(mu, *v, g);
+    step = vn;
+    if (nesterov)
+        step = fmaf(mu, vn, g);
+    *v = vn;
+    *w = fmaf(-lr, step, *w);
+}
+
 /*
  * One round over one bucket of n elements.
  *
@@ -56,6 +74,7 @@ static inline float widen_bf16(uint16_t h)
  *   mask         bit p set: process p is active in this round (s_t^p = true)
  *   w, v         parameters and momentum (fp32, n elements), updated in place; both may
  *                be NULL to skip the update rule
+ *   wd, nesterov variants of the update rule (0, 0 = heavy-ball momentum SGD)
  *   recv         receive buffer, gets the averaged result u; may be NULL
  *   nthreads     1 = the scalar reference; >1 = same loop body, elements partitioned
  *                statically over threads (per-element arithmetic and order unchanged)
@@ -63,11 +82,11 @@ static inline float widen_bf16(uint16_t h)
  * After the call the caller sets valid' = ~mask (on-time processes emptied their send
  * buffer, late ones stored the gradient they finished late).
  */
-void eager_oracle_round(int P, int64_t n,
-                        const void *const *G, int grad_is_bf16,
-                        float *const *R, uint64_t valid, uint64_t mask,
-                        float *w, float *v, float lr, float mu,
-                        float *recv, int nthreads)
+void eager_oracle_round_ex(int P, int64_t n,
+                           const void *const *G, int grad_is_bf16,
+                           float *const *R, uint64_t valid, uint64_t mask,
+                           float *w, float *v, float lr, float mu, float wd, int nesterov,
+                           float *recv, int nthreads)
 {
     const float inv_P = 1.0f / (float)P;
     int64_t i;
@@ -96,28 +115,38 @@ void eager_oracle_round(int P, int64_t n,
         }
         {
             const float u = s * inv_P;
-            if (w) {
-                const float vn = fmaf(mu, v[i], u);
-                v[i] = vn;
-                w[i] = fmaf(-lr, vn, w[i]);
-            }
+            if (w)
+                update_rule(u, &w[i], &v[i], lr, mu, wd, nesterov);
             if (recv)
                 recv[i] = u;
         }
     }
 }
 
+void eager_oracle_round(int P, int64_t n,
+                        const void *const *G, int grad_is_bf16,
+                        float *const *R, uint64_t valid, uint64_t mask,
+                        float *w, float *v, float lr, float mu,
+                        float *recv, int nthreads)
+{
+    eager_oracle_round_ex(P, n, G, grad_is_bf16, R, valid, mask, w, v, lr, mu, 0.0f, 0, recv,
+                          nthreads);
+}
+
 /* The update rule alone, applied to an already averaged result u (the unfused path:
  * receive buffer first, optimizer afterwards). */
-void eager_oracle_sgd(int64_t n, const float *u, float *w, float *v, float lr, float mu,
-                      int nthreads)
+void eager_oracle_sgd_ex(int64_t n, const float *u, float *w, float *v, float lr, float mu,
+                         float wd, int nesterov, int nthreads)
 {
     int64_t i;
     (void)nthreads;
 #pragma omp parallel for schedule(static) num_threads(nthreads) if (nthreads > 1)
-    for (i = 0; i < n; ++i) {
-        const float vn = fmaf(mu, v[i], u[i]);
-        v[i] = vn;
-        w[i] = fmaf(-lr, vn, w[i]);
-    }
+    for (i = 0; i < n; ++i)
+        update_rule(u[i], &w[i], &v[i], lr, mu, wd, nesterov);
+}
+
+void eager_oracle_sgd(int64_t n, const float *u, float *w, float *v, float lr, float mu,
+                      int nthreads)
+{
+    eager_oracle_sgd_ex(n, u, w, v, lr, mu, 0.0f, 0, nthreads);
 }

@@ -54,6 +54,16 @@ def _load():
             ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64, ctypes.c_uint64,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
             ctypes.c_void_p, ctypes.c_int]
+        lib.eager_oracle_round_ex.restype = None
+        lib.eager_oracle_round_ex.argtypes = [
+            ctypes.c_int, ctypes.c_int64, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+            ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64, ctypes.c_uint64,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
+            ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_int]
+        lib.eager_oracle_sgd_ex.restype = None
+        lib.eager_oracle_sgd_ex.argtypes = [
+            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int, ctypes.c_int]
         lib.eager_oracle_sgd.restype = None
         lib.eager_oracle_sgd.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -140,9 +150,11 @@ def _ptr_array(arrs: Sequence[np.ndarray]):
 
 def round_f32(G: Sequence[np.ndarray], R: Sequence[np.ndarray], valid: int, mask: int,
               w: Optional[np.ndarray], v: Optional[np.ndarray], lr: float, mu: float,
-              recv: Optional[np.ndarray] = None, nthreads: int = 1) -> int:
+              recv: Optional[np.ndarray] = None, nthreads: int = 1,
+              wd: float = 0.0, nesterov: bool = False) -> int:
     """One round on one bucket, in place.  G[p]: float32 or uint16 (bf16 bit patterns);
-    R[p], w, v, recv: float32.  Returns the new validity mask (~mask over P bits)."""
+    R[p], w, v, recv: float32.  wd, nesterov: variants of the update rule (off by
+    default).  Returns the new validity mask (~mask over P bits)."""
     P = len(G)
     n = G[0].shape[0]
     bf16 = G[0].dtype == np.uint16
@@ -153,19 +165,19 @@ def round_f32(G: Sequence[np.ndarray], R: Sequence[np.ndarray], valid: int, mask
     for x in (w, v, recv):
         assert x is None or (x.dtype == np.float32 and x.shape == (n,) and x.flags.c_contiguous)
     assert (w is None) == (v is None)
-    _load().eager_oracle_round(
+    _load().eager_oracle_round_ex(
         P, n, _ptr_array(G), int(bf16), _ptr_array(R), valid & _M64, mask & _M64,
         None if w is None else w.ctypes.data, None if v is None else v.ctypes.data,
-        lr, mu, None if recv is None else recv.ctypes.data, nthreads)
+        lr, mu, wd, int(nesterov), None if recv is None else recv.ctypes.data, nthreads)
     return ~mask & ((1 << P) - 1)
 
 
 def sgd_f32(u: np.ndarray, w: np.ndarray, v: np.ndarray, lr: float, mu: float,
-            nthreads: int = 1) -> None:
+            nthreads: int = 1, wd: float = 0.0, nesterov: bool = False) -> None:
     for x in (u, w, v):
         assert x.dtype == np.float32 and x.shape == u.shape and x.flags.c_contiguous
-    _load().eager_oracle_sgd(u.shape[0], u.ctypes.data, w.ctypes.data, v.ctypes.data,
-                             lr, mu, nthreads)
+    _load().eager_oracle_sgd_ex(u.shape[0], u.ctypes.data, w.ctypes.data, v.ctypes.data,
+                                lr, mu, wd, int(nesterov), nthreads)
 
 
 # --------------------------------------------------------------------------- fp64 (numpy)
@@ -205,8 +217,10 @@ class OracleState:
     3), so a round may be applied to any bucket range."""
 
     def __init__(self, P: int, offset: Sequence[int], numel: Sequence[int],
-                 arena_numel: int, w0: np.ndarray, lr: float, mu: float):
+                 arena_numel: int, w0: np.ndarray, lr: float, mu: float,
+                 wd: float = 0.0, nesterov: bool = False):
         self.P, self.lr, self.mu = P, float(lr), float(mu)
+        self.wd, self.nesterov = float(wd), bool(nesterov)
         self.offset, self.numel = list(offset), list(numel)
         self.w = np.ascontiguousarray(w0, dtype=np.float32).copy()
         assert self.w.shape == (arena_numel,)
@@ -223,11 +237,13 @@ class OracleState:
             self.valid[b] = round_f32(
                 [g[lo:hi] for g in G], [r[lo:hi] for r in self.R], self.valid[b], mask,
                 self.w[lo:hi] if fused else None, self.v[lo:hi] if fused else None,
-                self.lr, self.mu, None if recv is None else recv[lo:hi], nthreads)
+                self.lr, self.mu, None if recv is None else recv[lo:hi], nthreads,
+                self.wd, self.nesterov)
 
     def sgd(self, u: np.ndarray, b0: int = 0, b1: Optional[int] = None,
             nthreads: int = 1) -> None:
         b1 = len(self.numel) if b1 is None else b1
         for b in range(b0, b1):
             lo, hi = self.offset[b], self.offset[b] + self.numel[b]
-            sgd_f32(u[lo:hi], self.w[lo:hi], self.v[lo:hi], self.lr, self.mu, nthreads)
+            sgd_f32(u[lo:hi], self.w[lo:hi], self.v[lo:hi], self.lr, self.mu, nthreads,
+                    self.wd, self.nesterov)

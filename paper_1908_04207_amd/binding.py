@@ -25,7 +25,7 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_sgd_step", "eager_get_valid",
+    "eager_sgd_step", "eager_set_update_rule", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
 )
 
@@ -83,6 +83,7 @@ def _load() -> ctypes.CDLL:
     lib.eager_get_valid.argtypes = [vp, i32, ctypes.POINTER(u64)]
     lib.eager_set_valid.argtypes = [vp, i32, u64]
     lib.eager_set_launch.argtypes = [vp, ctypes.c_char_p, i32]
+    lib.eager_set_update_rule.argtypes = [vp, ctypes.c_float, i32]
     lib.eager_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.eager_calib_read.argtypes = [vp, i64, vp, vp]
     return lib
@@ -221,6 +222,10 @@ class Context:
 
     def eager_set_valid(self, bucket: int, valid_mask: int) -> None:
         self._check(lib.eager_set_valid(self._h, bucket, valid_mask), "eager_set_valid")
+
+    def eager_set_update_rule(self, weight_decay: float = 0.0, nesterov: bool = False) -> None:
+        self._check(lib.eager_set_update_rule(self._h, weight_decay, int(nesterov)),
+                    "eager_set_update_rule")
 
     def eager_set_launch(self, key: str, value: int) -> None:
         self._check(lib.eager_set_launch(self._h, key.encode(), value), "eager_set_launch")

@@ -22,6 +22,8 @@ struct eager_ctx {
     std::vector<uint64_t> last_step;   // per bucket: round it was last stepped with
     std::vector<uint8_t> stepped;      // per bucket: last_step is meaningful
     eager::Launch launch;
+    float weight_decay = 0.0f;         // update rule variants (eager_set_update_rule)
+    int nesterov = 0;
     std::string err;
 };
 
@@ -141,6 +143,8 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
     a.inv_P = 1.0f / static_cast<float>(P);
     a.neg_lr = opt ? -opt->lr : 0.0f;
     a.mu = opt ? opt->mu : 0.0f;
+    a.wd = ctx->weight_decay;
+    a.nesterov = ctx->nesterov;
 
     // Consecutive buckets whose send buffers are in the same state form one run = one
     // launch over a contiguous element range (after a whole-model round every bucket is
@@ -361,6 +365,8 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const ea
     a.n = ctx->offset[b1 - 1] + ctx->numel[b1 - 1] - ctx->offset[b0];
     a.neg_lr = -opt->lr;
     a.mu = opt->mu;
+    a.wd = ctx->weight_decay;
+    a.nesterov = ctx->nesterov;
     hipError_t he = eager::launch_sgd(a, ctx->fast, ctx->launch, static_cast<hipStream_t>(stream));
     if (he != hipSuccess)
         return fail(ctx, EAGER_EDEVICE, "sgd kernel launch failed: %s", hipGetErrorString(he));
@@ -382,6 +388,17 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask)
     if (valid_mask & ~low_bits(ctx->P)) return fail(ctx, EAGER_EINVAL, "validity mask has bits beyond P");
     ctx->valid[bucket] = valid_mask;
     ctx->stepped[bucket] = 0;
+    return EAGER_OK;
+}
+
+int eager_set_update_rule(eager_ctx *ctx, float weight_decay, int nesterov)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!(weight_decay >= 0.0f) || std::isinf(weight_decay))
+        return fail(ctx, EAGER_EINVAL, "weight_decay must be finite and >= 0");
+    if (nesterov != 0 && nesterov != 1) return fail(ctx, EAGER_EINVAL, "nesterov must be 0 or 1");
+    ctx->weight_decay = weight_decay;
+    ctx->nesterov = nesterov;
     return EAGER_OK;
 }
 

@@ -32,6 +32,8 @@ struct RoundArgs {
     float inv_P;                 // 1.0f / (float)P
     float neg_lr;                // -lr
     float mu;
+    float wd;                    // weight decay (0: none)
+    int nesterov;                // 1: Nesterov momentum
 };
 
 // The same round with the streams compacted.  Slot k is one stream and one action; slots are
@@ -56,7 +58,8 @@ struct SlotArgs {
     int n_slots;
     float *w, *v, *recv;
     long long e0, n;
-    float inv_P, neg_lr, mu;
+    float inv_P, neg_lr, mu, wd;
+    int nesterov;
 };
 
 // The carry as a kernel of its own: R_p <- G_p for every late process, one (source,
@@ -77,6 +80,8 @@ struct SgdArgs {
     long long n;
     float neg_lr;
     float mu;
+    float wd;
+    int nesterov;
 };
 
 struct Launch {

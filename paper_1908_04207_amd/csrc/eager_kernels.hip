@@ -72,6 +72,60 @@ __device__ __forceinline__ f32x4 widen_lo(u32x4 x, int half)   // elements 0..3 
     return r;
 }
 
+// The update rule U of Algorithm 2, lines 7-8, for one element or one vector of 4:
+//   g = u + wd*w  (only if wd != 0);  v' = mu*v + g;  step = nesterov ? g + mu*v' : v';
+//   w' = w - lr*step
+// every line one fused multiply-add (single rounding) in fixed-order mode.  wd and nesterov
+// are uniform over the grid; with wd = 0 and nesterov = 0 this is plain heavy-ball momentum.
+struct UpdateRule {
+    float neg_lr, mu, wd;
+    int nesterov;
+};
+
+__device__ __forceinline__ float fma1(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ f32x4 fma4(float a, f32x4 b, f32x4 c)
+{
+    f32x4 r;
+    r.x = __builtin_fmaf(a, b.x, c.x);
+    r.y = __builtin_fmaf(a, b.y, c.y);
+    r.z = __builtin_fmaf(a, b.z, c.z);
+    r.w = __builtin_fmaf(a, b.w, c.w);
+    return r;
+}
+
+template <bool FAST>
+__device__ __forceinline__ void update_rule(const UpdateRule &r, f32x4 u, f32x4 vo, f32x4 wo,
+                                            f32x4 &vn, f32x4 &wn)
+{
+    if (FAST) {
+#pragma clang fp contract(fast)
+        f32x4 g = u;
+        if (r.wd != 0.0f) g = r.wd * wo + u;
+        vn = r.mu * vo + g;
+        f32x4 step = vn;
+        if (r.nesterov) step = r.mu * vn + g;
+        wn = r.neg_lr * step + wo;
+    } else {
+        f32x4 g = u;
+        if (r.wd != 0.0f) g = fma4(r.wd, wo, u);
+        vn = fma4(r.mu, vo, g);
+        f32x4 step = vn;
+        if (r.nesterov) step = fma4(r.mu, vn, g);
+        wn = fma4(r.neg_lr, step, wo);
+    }
+}
+
+__device__ __forceinline__ void update_rule_scalar(const UpdateRule &r, float u, float &v, float &w)
+{
+    float g = u;
+    if (r.wd != 0.0f) g = fma1(r.wd, w, u);
+    const float vn = fma1(r.mu, v, g);
+    float step = vn;
+    if (r.nesterov) step = fma1(r.mu, vn, g);
+    v = vn;
+    w = fma1(r.neg_lr, step, w);
+}
+
 // One thread-vector: W = 4 (fp32 gradients) or 8 (bf16 gradients) consecutive elements,
 // i.e. NV = W/4 fp32 quads of state; U vectors are processed together.  Ranks are taken
 // CH at a time.
@@ -201,23 +255,9 @@ __device__ __forceinline__ void round_vectors(KRoundArgs &a, const long long (&e
             const long long i = e[u] + 4 * k;
             if (a.recv) st_f4<false>(a.recv + i, avg);
             if (a.w) {
-                const f32x4 vo = vo_[u][k];
-                const f32x4 wo = wo_[u][k];
                 f32x4 vn, wn;
-                if (FAST) {
-#pragma clang fp contract(fast)
-                    vn = a.mu * vo + avg;
-                    wn = a.neg_lr * vn + wo;
-                } else {
-                    vn.x = __builtin_fmaf(a.mu, vo.x, avg.x);
-                    vn.y = __builtin_fmaf(a.mu, vo.y, avg.y);
-                    vn.z = __builtin_fmaf(a.mu, vo.z, avg.z);
-                    vn.w = __builtin_fmaf(a.mu, vo.w, avg.w);
-                    wn.x = __builtin_fmaf(a.neg_lr, vn.x, wo.x);
-                    wn.y = __builtin_fmaf(a.neg_lr, vn.y, wo.y);
-                    wn.z = __builtin_fmaf(a.neg_lr, vn.z, wo.z);
-                    wn.w = __builtin_fmaf(a.neg_lr, vn.w, wo.w);
-                }
+                const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+                update_rule<FAST>(rule, avg, vo_[u][k], wo_[u][k], vn, wn);
                 st_f4<false>(a.v + i, vn);
                 st_f4<false>(a.w + i, wn);
             }
@@ -256,9 +296,11 @@ __device__ __forceinline__ void round_scalar(KRoundArgs &a, long long i)
     const float avg = s * a.inv_P;
     if (a.recv) a.recv[i] = avg;
     if (a.w) {
-        const float vn = __builtin_fmaf(a.mu, a.v[i], avg);
-        a.v[i] = vn;
-        a.w[i] = __builtin_fmaf(a.neg_lr, vn, a.w[i]);
+        const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+        float v = a.v[i], w = a.w[i];
+        update_rule_scalar(rule, avg, v, w);
+        a.v[i] = v;
+        a.w[i] = w;
     }
 }
 
@@ -448,20 +490,8 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U
         if (a.recv) st_f4<NTS>(a.recv + e, avg);
         if (a.w) {
             f32x4 vn, wn;
-            if (FAST) {
-#pragma clang fp contract(fast)
-                vn = a.mu * vo[u] + avg;
-                wn = a.neg_lr * vn + wo[u];
-            } else {
-                vn.x = __builtin_fmaf(a.mu, vo[u].x, avg.x);
-                vn.y = __builtin_fmaf(a.mu, vo[u].y, avg.y);
-                vn.z = __builtin_fmaf(a.mu, vo[u].z, avg.z);
-                vn.w = __builtin_fmaf(a.mu, vo[u].w, avg.w);
-                wn.x = __builtin_fmaf(a.neg_lr, vn.x, wo[u].x);
-                wn.y = __builtin_fmaf(a.neg_lr, vn.y, wo[u].y);
-                wn.z = __builtin_fmaf(a.neg_lr, vn.z, wo[u].z);
-                wn.w = __builtin_fmaf(a.neg_lr, vn.w, wo[u].w);
-            }
+            const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+            update_rule<FAST>(rule, avg, vo[u], wo[u], vn, wn);
             st_f4<NTS>(a.v + e, vn);
             st_f4<NTS>(a.w + e, wn);
         }
@@ -490,9 +520,11 @@ __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
     const float avg = s * a.inv_P;
     if (a.recv) a.recv[i] = avg;
     if (a.w) {
-        const float vn = __builtin_fmaf(a.mu, a.v[i], avg);
-        a.v[i] = vn;
-        a.w[i] = __builtin_fmaf(a.neg_lr, vn, a.w[i]);
+        const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+        float v = a.v[i], w = a.w[i];
+        update_rule_scalar(rule, avg, v, w);
+        a.v[i] = v;
+        a.w[i] = w;
     }
 }
 
@@ -587,29 +619,19 @@ __global__ __launch_bounds__(256) void sgd_kernel(const SgdArgs a)
         const f32x4 vo = ld_f4<false>(a.v + i);
         const f32x4 wo = ld_f4<false>(a.w + i);
         f32x4 vn, wn;
-        if (FAST) {
-#pragma clang fp contract(fast)
-            vn = a.mu * vo + u;
-            wn = a.neg_lr * vn + wo;
-        } else {
-            vn.x = __builtin_fmaf(a.mu, vo.x, u.x);
-            vn.y = __builtin_fmaf(a.mu, vo.y, u.y);
-            vn.z = __builtin_fmaf(a.mu, vo.z, u.z);
-            vn.w = __builtin_fmaf(a.mu, vo.w, u.w);
-            wn.x = __builtin_fmaf(a.neg_lr, vn.x, wo.x);
-            wn.y = __builtin_fmaf(a.neg_lr, vn.y, wo.y);
-            wn.z = __builtin_fmaf(a.neg_lr, vn.z, wo.z);
-            wn.w = __builtin_fmaf(a.neg_lr, vn.w, wo.w);
-        }
+        const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+        update_rule<FAST>(rule, u, vo, wo, vn, wn);
         st_f4<false>(a.v + i, vn);
         st_f4<false>(a.w + i, wn);
     }
     const long long rem = a.n - nvec * 4;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem) {
         const long long i = a.e0 + nvec * 4 + threadIdx.x;
-        const float vn = __builtin_fmaf(a.mu, a.v[i], a.u[i]);
-        a.v[i] = vn;
-        a.w[i] = __builtin_fmaf(a.neg_lr, vn, a.w[i]);
+        const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+        float v = a.v[i], w = a.w[i];
+        update_rule_scalar(rule, a.u[i], v, w);
+        a.v[i] = v;
+        a.w[i] = w;
     }
 }
 
@@ -728,6 +750,8 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
     s.inv_P = a.inv_P;
     s.neg_lr = a.neg_lr;
     s.mu = a.mu;
+    s.wd = a.wd;
+    s.nesterov = a.nesterov;
 }
 
 // Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of

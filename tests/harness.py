@@ -44,7 +44,8 @@ class Pair:
     def __init__(self, eb, P: int, offset: Sequence[int], numel: Sequence[int],
                  arena_numel: int, grad_dtype: str = "f32", order: int = 0,
                  lr: float = 0.1, mu: float = 0.9, seed: int = 1,
-                 grad_sigma: float = 1e-3, param_sigma: float = 0.02, poison: bool = True):
+                 grad_sigma: float = 1e-3, param_sigma: float = 0.02, poison: bool = True,
+                 wd: float = 0.0, nesterov: bool = False):
         self.eb, self.P, self.seed = eb, P, seed
         self.offset, self.numel, self.arena = list(offset), list(numel), arena_numel
         self.dtype = NT_DTYPE[grad_dtype]
@@ -60,7 +61,10 @@ class Pair:
                   for _ in range(P)]
         self.G = [torch.empty(arena_numel, dtype=self.dtype, device=dev) for _ in range(P)]
         self.recv = torch.empty(arena_numel, device=dev)
-        self.oracle = eo.OracleState(P, self.offset, self.numel, arena_numel, w0.numpy(), lr, mu)
+        if wd or nesterov:
+            self.ctx.eager_set_update_rule(wd, nesterov)
+        self.oracle = eo.OracleState(P, self.offset, self.numel, arena_numel, w0.numpy(), lr, mu,
+                                     wd, nesterov)
         self.oracle_recv = np.zeros(arena_numel, dtype=np.float32)
         self.step_no = 0
 

@@ -81,6 +81,29 @@ def test_rank_counts_and_random_masks(eb, P, dtype):
         pair.compare(exact=True, check_recv=True, what=f"P={P} {dtype} t={t} mask={mask:#x}")
 
 
+@pytest.mark.parametrize("dtype,order", [("f32", 0), ("bf16", 0), ("f32", 1)])
+@pytest.mark.parametrize("wd,nesterov", [(0.0, True), (0.05, False), (0.01, True)])
+def test_update_rule_variants(eb, dtype, order, wd, nesterov):
+    """Weight decay and Nesterov momentum in the fused pass and in eager_sgd_step, bitwise
+    in fixed-order mode."""
+    cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 2), 1500)
+    bt = cfg.buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, order, cfg.lr, cfg.mu,
+                seed=21, wd=wd, nesterov=nesterov)
+    for t in range(5):
+        plan = plan_for(eb, cfg, t)
+        G = pair.fresh_grads(t)
+        if t == 3:                      # one unfused round: receive buffer, then the rule alone
+            pair.round(plan, G, fused=False)
+            pair.sgd()
+        else:
+            pair.round(plan, G, want_recv=True)
+        pair.compare(exact=(order == 0), tol=_tol(dtype), check_recv=True,
+                     what=f"wd={wd} nesterov={nesterov} {dtype} t={t}")
+    with pytest.raises(eb.EagerError):
+        pair.ctx.eager_set_update_rule(-1.0, False)
+
+
 def test_quorum_rounds(eb):
     """k-of-P participation through eager_plan_quorum / eager_partial_allreduce_quorum, k
     sweeping from solo to full, on the LSTM layout; bitwise."""

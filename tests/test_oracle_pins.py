@@ -234,6 +234,40 @@ def test_momentum_closed_form_and_plain_sgd():
     assert np.array_equal(w2, w3) and np.array_equal(v2, v3)
 
 
+@pytest.mark.parametrize("wd,nesterov", [(0.0, True), (0.05, False), (0.01, True)])
+def test_update_rule_variants_against_torch_sgd(wd, nesterov):
+    """Weight decay and Nesterov momentum (variants of the generic U of Algorithm 2 line 7)
+    follow torch.optim.SGD (library routine) over several steps with everybody on time;
+    the variants change nothing of the carry (send buffers stay empty)."""
+    import torch
+    P, n, T, lr, mu = 4, 257, 6, 0.05, 0.9
+    rng = np.random.default_rng(5)
+    w0 = rng.standard_normal(n).astype(np.float32)
+    w, v = w0.copy(), np.zeros(n, dtype=np.float32)
+    tw = torch.tensor(w0.copy(), requires_grad=True)
+    opt = torch.optim.SGD([tw], lr=lr, momentum=mu, weight_decay=wd, nesterov=nesterov)
+    R, valid = _empty_R(P, n), 0
+    for t in range(T):
+        G = [rng.standard_normal(n).astype(np.float32) for _ in range(P)]
+        valid = eo.round_f32(G, R, valid, (1 << P) - 1, w, v, lr, mu, wd=wd, nesterov=nesterov)
+        assert valid == 0
+        tw.grad = torch.tensor(np.mean(np.stack(G).astype(np.float64), axis=0).astype(np.float32))
+        opt.step()
+        assert np.allclose(w, tw.detach().numpy(), rtol=0, atol=2e-6), t
+    # closed form, one step from v = 0:  g = u + wd w ;  v = g ;  w' = w - lr (1 + mu) g  (Nesterov)
+    w1, v1 = w0.copy(), np.zeros(n, dtype=np.float32)
+    u = rng.standard_normal(n).astype(np.float32)
+    eo.sgd_f32(u, w1, v1, lr, mu, wd=wd, nesterov=nesterov)
+    g = u.astype(np.float64) + wd * w0
+    want = w0 - lr * ((1 + mu) * g if nesterov else g)
+    assert np.allclose(v1, g, rtol=1e-6, atol=1e-7) and np.allclose(w1, want, rtol=1e-6, atol=1e-6)
+    # the variants switched off are the plain rule, bit for bit
+    w2, v2, w3, v3 = w0.copy(), v1.copy(), w0.copy(), v1.copy()
+    eo.sgd_f32(u, w2, v2, lr, mu)
+    eo.sgd_f32(u, w3, v3, lr, mu, wd=0.0, nesterov=False)
+    assert np.array_equal(w2, w3) and np.array_equal(v2, v3)
+
+
 def test_divides_by_P_not_by_contributors():
     """Algorithm 2 line 6 scales by 1/P whatever the number of active processes.  With
     fresh = 1 and null = 0 the delivered value times P is the number of active
