@@ -64,7 +64,7 @@ class Workload:
     generator (outside any timed region)."""
 
     def __init__(self, k: int, order: str, launch: dict | None = None, stagger: int = 0,
-                 clip: int = 0):
+                 clip: int = 0, stats: bool = False):
         import torch
         from paper_1908_04207_amd import binding as eb
         from workloads import grads as wg
@@ -94,6 +94,11 @@ class Workload:
             self.R[p].zero_()
         self.w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
         self.v = torch.zeros(n, device=dev)
+        if stats:      # optional per-bucket by-products (norms), computed in the same pass
+            nbytes = self.ctx.eager_stats_workspace_bytes()
+            self.stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
+            self.stats_ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            self.ctx.eager_stats_attach(self.stats, self.stats_ws, nbytes)
         self.step_no = 0
         self.q_prev = 0
         torch.cuda.synchronize()
@@ -118,13 +123,14 @@ class Workload:
         return b
 
 
-def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0, clip=0):
+def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0, clip=0,
+            stats=False):
     """W untimed steps, then K timed steps.  Returns the workload, the wall-clock seconds
     of the K steps (synchronised on both sides), their algorithmic bytes, and the GPU time
     of the same K steps between two HIP events recorded on the launch stream (torch's
     current stream, which is the one the binding launches on)."""
     import torch
-    wl = Workload(k, order, launch, stagger, clip)
+    wl = Workload(k, order, launch, stagger, clip, stats)
     for _ in range(warmup):
         wl.step()
     torch.cuda.synchronize()
@@ -236,6 +242,8 @@ def main() -> int:
     ap.add_argument("--clip", type=int, default=0,
                     help="clip every tensor to this many elements (a reduced layout of the same "
                          "configuration, for counter runs the profiler cannot take at full size)")
+    ap.add_argument("--stats", action="store_true",
+                    help="also compute the per-bucket norms in every round (eager_stats_attach)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (P simulated processes share its HBM); "
@@ -247,7 +255,7 @@ def main() -> int:
         return 2
     launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
     wl, wall, nbytes, kern_s = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger,
-                                       a.clip)
+                                       a.clip, a.stats)
     cfg = wl.cfg
     total_b = sum(nbytes)
     traffic = MEASURED_TRAFFIC.get(cfg.name)
@@ -262,7 +270,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode,
                    "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
-                   "order": a.order, "launch": launch, "stagger": a.stagger},
+                   "order": a.order, "launch": launch, "stagger": a.stagger,
+                   "bucket_stats": a.stats},
         "steps_per_s": round(a.steps / wall, 2),
         "pct_hbm_peak": round(100.0 * total_b / wall / 1e9 / HBM_PEAK_GBS, 2),
         "alg_bytes_per_step": round(total_b / a.steps),

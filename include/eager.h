@@ -177,6 +177,42 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update,
  */
 int eager_set_update_rule(eager_ctx *ctx, float weight_decay, int nesterov);
 
+/*
+ * Optional per-bucket by-products of a round, computed in the same pass over HBM (what
+ * layer-wise update rules and gradient-norm monitoring need; U is generic in the paper):
+ *   sumsq_update  sum of u_i^2 over the bucket's elements with finite u_i, u = the averaged
+ *                 result of the round (Algorithm 2 line 6); squares and sums in fp64
+ *   sumsq_params  the same over the parameters w_i BEFORE the update (0 without opt)
+ *   nonfinite     number of elements whose u_i is NaN or infinite
+ * Sums are reproducible from run to run except in the wavefronts that hold a bucket boundary
+ * (their lanes add atomically, in arbitrary order); compare with a tolerance.
+ */
+typedef struct {
+    double   sumsq_update;
+    double   sumsq_params;
+    uint64_t nonfinite;
+    uint64_t reserved;
+} eager_bucket_stats;
+
+/*
+ * eager_stats_attach: from now on every eager_partial_allreduce_* call of this context also
+ * writes stats[b] for each bucket b it covers (overwritten by every call).
+ *   stats      device array of n_buckets entries, 16-byte aligned, caller-owned; NULL detaches
+ *   workspace  device memory, 16-byte aligned, caller-owned, at least
+ *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table and one
+ *              32-byte record per wavefront of the round kernel there.  It must stay
+ *              allocated, and must not be shared with another context that runs concurrently,
+ *              while attached
+ *   stream     the bucket table is uploaded on this stream (asynchronously; rounds that
+ *              use the statistics must be ordered after it, e.g. on the same stream)
+ * Needs the compact path with its default chunk size ("compact" = 1, "chunk" = 0 or 16);
+ * otherwise the next round fails with ESTATE.  Two extra small kernels run per call.
+ * Errors: EINVAL (NULL ctx, workspace too small or misaligned), ENOMEM, EDEVICE.
+ */
+int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes);
+int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspace,
+                       int64_t workspace_bytes, void *stream);
+
 /* Send-buffer validity of one bucket (bit p: R_p holds an undelivered gradient);
  * together with w, v, R and the round index this is all the state a resume needs. */
 int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask);

@@ -10,6 +10,7 @@ Contents
   round_f64            the same recurrence in numpy fp64, written independently of the C
                        file; used to pin the C code and to bound fp32 rounding
   OracleState          per-bucket bookkeeping of send-buffer validity over many rounds
+  bucket_stats         per-bucket by-products of a round (norms of update and parameters)
 """
 from __future__ import annotations
 
@@ -247,3 +248,22 @@ class OracleState:
             lo, hi = self.offset[b], self.offset[b] + self.numel[b]
             sgd_f32(u[lo:hi], self.w[lo:hi], self.v[lo:hi], self.lr, self.mu, nthreads,
                     self.wd, self.nesterov)
+
+
+# --------------------------------------------------------------------------- by-products
+def bucket_stats(u: np.ndarray, w_before: Optional[np.ndarray], offset: Sequence[int],
+                 numel: Sequence[int]):
+    """Per bucket: sum of u_i^2 over finite u_i, sum of w_i^2 over finite w_i (parameters
+    before the update; 0 if None), number of non-finite u_i.  Plain fp64 numpy over each
+    bucket's slice; padding between buckets is not part of any bucket."""
+    out = []
+    for lo, n in zip(offset, numel):
+        ub = np.asarray(u[lo:lo + n], dtype=np.float64)
+        fin = np.isfinite(ub)
+        ssu = float(np.sum(np.square(ub[fin])))
+        ssw = 0.0
+        if w_before is not None:
+            wb = np.asarray(w_before[lo:lo + n], dtype=np.float64)
+            ssw = float(np.sum(np.square(wb[np.isfinite(wb)])))
+        out.append((ssu, ssw, int(n - np.count_nonzero(fin))))
+    return out

@@ -25,7 +25,8 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_sgd_step", "eager_set_update_rule", "eager_get_valid",
+    "eager_sgd_step", "eager_set_update_rule", "eager_stats_workspace_bytes",
+    "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
 )
 
@@ -84,6 +85,8 @@ def _load() -> ctypes.CDLL:
     lib.eager_set_valid.argtypes = [vp, i32, u64]
     lib.eager_set_launch.argtypes = [vp, ctypes.c_char_p, i32]
     lib.eager_set_update_rule.argtypes = [vp, ctypes.c_float, i32]
+    lib.eager_stats_workspace_bytes.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.eager_stats_attach.argtypes = [vp, vp, vp, i64, vp]
     lib.eager_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.eager_calib_read.argtypes = [vp, i64, vp, vp]
     return lib
@@ -226,6 +229,18 @@ class Context:
     def eager_set_update_rule(self, weight_decay: float = 0.0, nesterov: bool = False) -> None:
         self._check(lib.eager_set_update_rule(self._h, weight_decay, int(nesterov)),
                     "eager_set_update_rule")
+
+    def eager_stats_workspace_bytes(self) -> int:
+        n = ctypes.c_int64()
+        self._check(lib.eager_stats_workspace_bytes(self._h, ctypes.byref(n)),
+                    "eager_stats_workspace_bytes")
+        return n.value
+
+    def eager_stats_attach(self, stats, workspace, workspace_bytes: int = 0, stream=None) -> None:
+        """stats: device buffer of n_buckets x 32 bytes (sumsq_update f64, sumsq_params f64,
+        nonfinite u64, reserved u64), or None to detach; workspace: device buffer."""
+        self._check(lib.eager_stats_attach(self._h, _ptr(stats), _ptr(workspace), workspace_bytes,
+                                           _stream(stream)), "eager_stats_attach")
 
     def eager_set_launch(self, key: str, value: int) -> None:
         self._check(lib.eager_set_launch(self._h, key.encode(), value), "eager_set_launch")

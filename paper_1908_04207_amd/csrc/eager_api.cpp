@@ -24,6 +24,9 @@ struct eager_ctx {
     eager::Launch launch;
     float weight_decay = 0.0f;         // update rule variants (eager_set_update_rule)
     int nesterov = 0;
+    std::vector<long long> table;      // start, end of every bucket (uploaded by eager_stats_attach)
+    eager::BucketStats *stats = nullptr;   // device, caller-owned; NULL: no by-products
+    char *workspace = nullptr;             // device, caller-owned: bucket table, then records
     std::string err;
 };
 
@@ -145,6 +148,20 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
     a.mu = opt ? opt->mu : 0.0f;
     a.wd = ctx->weight_decay;
     a.nesterov = ctx->nesterov;
+    if (ctx->stats) {
+        if (ctx->launch.compact == 0 || (ctx->launch.chunk != 0 && ctx->launch.chunk != 16))
+            return fail(ctx, EAGER_ESTATE, "bucket statistics need compact = 1 and chunk = 16");
+        a.stats.table = reinterpret_cast<const long long *>(ctx->workspace);
+        a.stats.stats = ctx->stats;
+        a.stats.records = reinterpret_cast<eager::StatsRecord *>(
+            ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
+        a.stats.n_buckets = ctx->n_buckets;
+        a.stats.b_lo = b0;
+        a.stats.b_hi = b1;
+        hipError_t he = eager::launch_stats_zero(a.stats, static_cast<hipStream_t>(stream));
+        if (he != hipSuccess)
+            return fail(ctx, EAGER_EDEVICE, "statistics kernel launch failed: %s", hipGetErrorString(he));
+    }
 
     // Consecutive buckets whose send buffers are in the same state form one run = one
     // launch over a contiguous element range (after a whole-model round every bucket is
@@ -162,10 +179,22 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         const bool split = late != 0 && use_split(ctx->launch, ctx->bf16, P, plan->mask, a.valid);
         a.gload = split ? plan->mask : low_bits(P);
         a.store = split ? 0 : late;
+        if (ctx->stats) {
+            a.stats.e0 = a.e0;
+            a.stats.b_lo = b;
+            a.stats.b_hi = e;
+            a.stats.n_records = eager::slot_records(a.n, ctx->bf16, ctx->launch.block);
+        }
         hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
                                             static_cast<hipStream_t>(stream));
         if (he != hipSuccess)
             return fail(ctx, EAGER_EDEVICE, "round kernel launch failed: %s", hipGetErrorString(he));
+        if (ctx->stats) {
+            he = eager::launch_stats_finish(a.stats, static_cast<hipStream_t>(stream));
+            if (he != hipSuccess)
+                return fail(ctx, EAGER_EDEVICE, "statistics kernel launch failed: %s",
+                            hipGetErrorString(he));
+        }
         if (split) {
             // same stream: the reduction has read every pending R_p before it is overwritten
             eager::CarryArgs c;
@@ -388,6 +417,60 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask)
     if (valid_mask & ~low_bits(ctx->P)) return fail(ctx, EAGER_EINVAL, "validity mask has bits beyond P");
     ctx->valid[bucket] = valid_mask;
     ctx->stepped[bucket] = 0;
+    return EAGER_OK;
+}
+
+namespace {
+// wavefronts a round kernel may be launched with over the whole arena, whatever the block size
+int64_t max_records(const eager_ctx *ctx)
+{
+    const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
+    return span / 256 + 8;
+}
+}  // namespace
+
+int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes)
+{
+    if (!ctx || !bytes) return EAGER_EINVAL;
+    *bytes = static_cast<int64_t>(ctx->n_buckets) * 16 +
+             max_records(ctx) * static_cast<int64_t>(sizeof(eager::StatsRecord));
+    return EAGER_OK;
+}
+
+int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspace,
+                       int64_t workspace_bytes, void *stream)
+{
+    static_assert(sizeof(eager_bucket_stats) == sizeof(eager::BucketStats), "layout");
+    static_assert(sizeof(eager::StatsRecord) == 32, "layout");
+    if (!ctx) return EAGER_EINVAL;
+    if (!stats) {                       // detach
+        ctx->stats = nullptr;
+        ctx->workspace = nullptr;
+        return EAGER_OK;
+    }
+    int64_t need = 0;
+    eager_stats_workspace_bytes(ctx, &need);
+    if (!workspace || workspace_bytes < need)
+        return fail(ctx, EAGER_EINVAL, "statistics workspace must hold %lld bytes",
+                    static_cast<long long>(need));
+    if (!aligned16(stats) || !aligned16(workspace))
+        return fail(ctx, EAGER_EINVAL, "stats and workspace must be 16-byte aligned");
+    try {
+        ctx->table.resize(static_cast<size_t>(ctx->n_buckets) * 2);
+    } catch (const std::bad_alloc &) {
+        return fail(ctx, EAGER_ENOMEM, "out of host memory");
+    }
+    for (int b = 0; b < ctx->n_buckets; ++b) {
+        ctx->table[2 * b] = ctx->offset[b];
+        ctx->table[2 * b + 1] = ctx->offset[b] + ctx->numel[b];
+    }
+    // the table lives in the context, so it outlives the copy
+    hipError_t he = hipMemcpyAsync(workspace, ctx->table.data(), ctx->table.size() * 8,
+                                   hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+    if (he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "upload of the bucket table failed: %s", hipGetErrorString(he));
+    ctx->stats = reinterpret_cast<eager::BucketStats *>(stats);
+    ctx->workspace = static_cast<char *>(workspace);
     return EAGER_OK;
 }
 

@@ -9,6 +9,36 @@ namespace eager {
 
 constexpr int kMaxP = 64;
 
+// Optional by-products of a round, per bucket (same layout as eager_bucket_stats of the public
+// header): squared norm of the averaged update and of the parameters before the update (finite
+// elements only), number of non-finite elements of the update.
+struct BucketStats {
+    double sumsq_update;
+    double sumsq_params;
+    unsigned long long nonfinite;
+    unsigned long long reserved;
+};
+
+// What one wavefront of the round kernel leaves for the finishing kernel: the sums over its
+// 256 elements if they all lie in one bucket (bucket >= 0), else bucket = -1 (then its lanes
+// have added to the bucket totals themselves).
+struct StatsRecord {
+    double ssu, ssw;
+    int bucket;
+    unsigned nf;
+    long long pad;
+};
+
+struct StatsArgs {
+    const long long *table;      // device: start, end of every bucket (2 per bucket)
+    BucketStats *stats;          // device: one per bucket
+    StatsRecord *records;        // device: one per wavefront of the round kernel
+    long long e0;                // first element of the run
+    long long n_records;         // wavefronts the round kernel was launched with
+    int b_lo, b_hi;              // buckets of the run
+    int n_buckets;
+};
+
 // Everything one launch of the round kernel needs, passed by value in the kernel
 // argument segment: the P gradient and send-buffer bases stay in scalar registers and
 // every per-rank decision is uniform across the grid.
@@ -34,6 +64,7 @@ struct RoundArgs {
     float mu;
     float wd;                    // weight decay (0: none)
     int nesterov;                // 1: Nesterov momentum
+    StatsArgs stats;             // stats.stats == NULL: no by-products
 };
 
 // The same round with the streams compacted.  Slot k is one stream and one action; slots are
@@ -60,6 +91,7 @@ struct SlotArgs {
     long long e0, n;
     float inv_P, neg_lr, mu, wd;
     int nesterov;
+    StatsArgs stats;
 };
 
 // The carry as a kernel of its own: R_p <- G_p for every late process, one (source,
@@ -104,6 +136,9 @@ struct Launch {
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
 hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream);
+hipError_t launch_stats_zero(const StatsArgs &a, hipStream_t stream);
+hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
+long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

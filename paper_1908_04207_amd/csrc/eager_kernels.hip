@@ -346,6 +346,118 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs)
 // lanes 2k and 2k+1 load the same piece and each keeps its half.  That way every load of a
 // chunk is the same 16-byte instruction whatever the type of its stream - the type, like the
 // action, is a scalar select and never a branch around a load.
+// ---------------------------------------------------------------------------------------
+// Per-bucket by-products (optional): sum of squares of the averaged update and of the
+// parameters, count of non-finite elements.  They are reductions ACROSS elements, the one
+// place on this path where cross-lane work belongs: a lane sums its 4 elements, the 64 lanes
+// of a wavefront are combined with DPP moves inside rows of 16 lanes and lane reads across
+// the 4 rows, and one lane writes one record per wavefront (no atomics on the common path,
+// and a fixed tree: the result is reproducible).  A finishing kernel adds the records of a
+// bucket, combining the wavefronts of its workgroup through LDS.
+struct LaneStats {
+    double ssu, ssw;   // squares of the update / of the old parameters
+    unsigned nf;       // non-finite elements of the update
+    int bucket;        // -1: the lane holds no element
+};
+
+// DPP controls: quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.  Applied
+// in this order every lane ends with the sum over its row of 16; all lanes must be active.
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x)
+{
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, x);
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(b), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(b >> 32), CTRL, 0xf, 0xf, true);
+    return __builtin_bit_cast(double, (static_cast<unsigned long long>(static_cast<unsigned>(hi)) << 32) |
+                                          static_cast<unsigned>(lo));
+}
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_u32(unsigned x)
+{
+    return static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ double readlane_f64(double x, int lane)
+{
+    const unsigned long long b = __builtin_bit_cast(unsigned long long, x);
+    const unsigned lo = __builtin_amdgcn_readlane(static_cast<int>(b), lane);
+    const unsigned hi = __builtin_amdgcn_readlane(static_cast<int>(b >> 32), lane);
+    return __builtin_bit_cast(double, (static_cast<unsigned long long>(hi) << 32) | lo);
+}
+// sum over the 64 lanes of the wavefront, the same value in every lane (uniform)
+__device__ __forceinline__ double wave_sum(double x)
+{
+    x = x + dpp_f64<kDppXor1>(x);
+    x = x + dpp_f64<kDppXor2>(x);
+    x = x + dpp_f64<kDppHalfMirror>(x);
+    x = x + dpp_f64<kDppMirror>(x);
+    return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
+}
+__device__ __forceinline__ unsigned wave_sum(unsigned x)
+{
+    x = x + dpp_u32<kDppXor1>(x);
+    x = x + dpp_u32<kDppXor2>(x);
+    x = x + dpp_u32<kDppHalfMirror>(x);
+    x = x + dpp_u32<kDppMirror>(x);
+    return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(x), 0)) +
+           static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(x), 16)) +
+           static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(x), 32)) +
+           static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(x), 48));
+}
+
+// the bucket that holds element e: the last one that starts at or before e
+__device__ __forceinline__ int find_bucket(const long long *tbl, int nb, long long e)
+{
+    int lo = 0, hi = nb;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tbl[2 * mid] <= e) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ void stats_add(LaneStats &ls, float u, float w_old, bool has_w)
+{
+    if (__builtin_isfinite(u)) ls.ssu += static_cast<double>(u) * static_cast<double>(u);
+    else ls.nf += 1u;
+    if (has_w && __builtin_isfinite(w_old))
+        ls.ssw += static_cast<double>(w_old) * static_cast<double>(w_old);
+}
+
+__device__ __forceinline__ void stats_atomic(BucketStats *st, const LaneStats &ls)
+{
+    if (ls.bucket < 0) return;
+    BucketStats *b = st + ls.bucket;
+    if (ls.ssu != 0.0)
+        __hip_atomic_fetch_add(&b->sumsq_update, ls.ssu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ls.ssw != 0.0)
+        __hip_atomic_fetch_add(&b->sumsq_params, ls.ssw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (ls.nf != 0u)
+        __hip_atomic_fetch_add(&b->nonfinite, static_cast<unsigned long long>(ls.nf),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Called by every lane of a wavefront (all active).  One record per wavefront; a wavefront
+// whose elements lie in several buckets (or that holds a ragged end) adds per lane instead.
+__device__ __forceinline__ void stats_commit(BucketStats *stats, StatsRecord *records,
+                                             const LaneStats &ls, long long wave_index)
+{
+    const int b0 = __builtin_amdgcn_readfirstlane(ls.bucket);
+    const bool mixed = __builtin_amdgcn_ballot_w64(ls.bucket != b0) != 0ull;
+    StatsRecord rec = {0.0, 0.0, -1, 0u, 0};
+    if (!mixed && b0 >= 0) {
+        rec.ssu = wave_sum(ls.ssu);
+        rec.ssw = wave_sum(ls.ssw);
+        rec.nf = wave_sum(ls.nf);
+        rec.bucket = b0;
+    } else if (mixed) {
+        stats_atomic(stats, ls);
+    }
+    if ((threadIdx.x & 63u) == 0u) records[wave_index] = rec;
+}
+
 struct LaneVec {
     long long e;        // first of the lane's 4 elements (arena index)
     long long off_bf;   // byte offset of the 16-byte piece of a bf16 stream that holds them
@@ -453,8 +565,9 @@ __device__ __forceinline__ void slot_remainder(KSlotArgs &a, int k0, int rem,
 
 // NTS: parameters, momentum and the receive buffer are streamed with the nontemporal hint
 // too (right when they are too large to stay in the last-level cache until the next round).
-template <bool BF16, bool FAST, bool NT, bool NTS, int U, int CH>
-__device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U])
+template <bool BF16, bool FAST, bool NT, bool NTS, int U, int CH, bool STATS>
+__device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U], int n_valid,
+                                             LaneStats &ls)
 {
     f32x4 s[U][2], hold[U];
 #pragma unroll
@@ -488,6 +601,16 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U
         if (FAST) sum = sum + s[u][1];
         const f32x4 avg = sum * a.inv_P;
         if (a.recv) st_f4<NTS>(a.recv + e, avg);
+        if (STATS) {
+            // n_valid: how many of the lane's 4 elements lie inside their bucket (the rest
+            // is padding between buckets)
+            const bool has_w = a.w != nullptr;
+            const f32x4 w_old = has_w ? wo[u] : (f32x4)(0.0f);
+            if (n_valid > 0) stats_add(ls, avg.x, w_old.x, has_w);
+            if (n_valid > 1) stats_add(ls, avg.y, w_old.y, has_w);
+            if (n_valid > 2) stats_add(ls, avg.z, w_old.z, has_w);
+            if (n_valid > 3) stats_add(ls, avg.w, w_old.w, has_w);
+        }
         if (a.w) {
             f32x4 vn, wn;
             const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
@@ -500,7 +623,7 @@ __device__ __forceinline__ void slot_vectors(KSlotArgs &a, const LaneVec (&lv)[U
 
 // ragged tail: at most 3 (7 with bf16 gradients) elements per launch, fixed order in both
 // modes
-template <bool BF16>
+template <bool BF16, bool STATS>
 __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
 {
     float s = 0.0f, hold = 0.0f;
@@ -519,6 +642,15 @@ __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
     }
     const float avg = s * a.inv_P;
     if (a.recv) a.recv[i] = avg;
+    if (STATS) {
+        // a handful of elements per launch: straight to the bucket totals
+        const long long *tbl = a.stats.table;
+        LaneStats ls = {0.0, 0.0, 0u, find_bucket(tbl, a.stats.n_buckets, i)};
+        if (i < tbl[2 * ls.bucket + 1]) {
+            stats_add(ls, avg, a.w ? a.w[i] : 0.0f, a.w != nullptr);
+            stats_atomic(a.stats.stats, ls);
+        }
+    }
     if (a.w) {
         const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
         float v = a.v[i], w = a.w[i];
@@ -540,21 +672,95 @@ __host__ __device__ __forceinline__ long long slot_nvec(long long n)
 // One lane-vector per lane and no loop over tiles: inside a loop every scalar condition of
 // every slot is loop invariant, the compiler hoists hundreds of them out of it and then
 // spills scalar registers.  The grid always covers the run.
-template <bool BF16, bool FAST, bool NT, bool NTS, int CH>
+template <bool BF16, bool FAST, bool NT, bool NTS, int CH, bool STATS>
 __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
 {
     KSlotArgs &a = kernarg<SlotArgs>();
     const long long nvec = slot_nvec<BF16>(a.n);
     const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    LaneStats ls = {0.0, 0.0, 0u, -1};
+    int n_valid = 0;
+    int wave_bucket = 0;
+    if (STATS) {
+        // bucket of the wavefront's first element: a uniform search (scalar loads), started
+        // before the streams are requested
+        const long long v0 = vi - (threadIdx.x & 63u);
+        const long long e_wave =
+            a.e0 + 4 * ((static_cast<long long>(__builtin_amdgcn_readfirstlane(
+                             static_cast<int>(v0 >> 32))) << 32) |
+                        static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v0))));
+        wave_bucket = find_bucket(a.stats.table, a.stats.n_buckets, e_wave);
+    }
     if (vi < nvec) {
         // bucket starts are multiples of 8 elements with bf16 gradients, so e0 * 2 is a
         // multiple of 16 bytes
         const LaneVec lv[1] = {{a.e0 + vi * 4, a.e0 * 2 + (vi >> 1) * 16, (vi & 1) != 0}};
-        slot_vectors<BF16, FAST, NT, NTS, 1, CH>(a, lv);
+        if (STATS) {
+            // a lane's 4 elements never straddle a bucket start (starts are multiples of 4)
+            const long long *tbl = a.stats.table;
+            int b = wave_bucket;
+            while (b + 1 < a.stats.n_buckets && tbl[2 * (b + 1)] <= lv[0].e) ++b;
+            const long long left = tbl[2 * b + 1] - lv[0].e;
+            n_valid = left >= 4 ? 4 : left > 0 ? static_cast<int>(left) : 0;
+            ls.bucket = b;
+        }
+        slot_vectors<BF16, FAST, NT, NTS, 1, CH, STATS>(a, lv, n_valid, ls);
     }
+    if (STATS) stats_commit(a.stats.stats, a.stats.records, ls, vi >> 6);
     const long long rem = a.n - nvec * 4;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
-        slot_scalar<BF16>(a, a.e0 + nvec * 4 + threadIdx.x);
+        slot_scalar<BF16, STATS>(a, a.e0 + nvec * 4 + threadIdx.x);
+}
+
+// stats[b] = 0 for the buckets a call covers (a kernel, not a memset, so that a caller may
+// capture the call in a graph)
+__global__ __launch_bounds__(256) void stats_zero_kernel(const StatsArgs a)
+{
+    const int b = a.b_lo + static_cast<int>(blockIdx.x * blockDim.x + threadIdx.x);
+    if (b < a.b_hi) {
+        const BucketStats z = {0.0, 0.0, 0ull, 0ull};
+        a.stats[b] = z;
+    }
+}
+
+// One workgroup per bucket of the run: adds the records of the wavefronts whose 256 elements
+// lie in the bucket (they are consecutive), wavefront sums by DPP, the 4 wavefronts of the
+// workgroup through LDS, then one thread adds the result to what lanes of mixed wavefronts
+// have already put there.
+__global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
+{
+    __shared__ double part_u[4], part_w[4];
+    __shared__ unsigned part_n[4];
+    const int b = a.b_lo + static_cast<int>(blockIdx.x);
+    const long long start = a.table[2 * b], end = a.table[2 * b + 1];
+    long long w0 = (start - a.e0) / 256, w1 = (end - a.e0 + 255) / 256;
+    if (w1 > a.n_records) w1 = a.n_records;
+    double su = 0.0, sw = 0.0;
+    unsigned nf = 0u;
+    for (long long w = w0 + threadIdx.x; w < w1; w += blockDim.x) {
+        const StatsRecord r = a.records[w];
+        if (r.bucket == b) {
+            su += r.ssu;
+            sw += r.ssw;
+            nf += r.nf;
+        }
+    }
+    su = wave_sum(su);
+    sw = wave_sum(sw);
+    nf = wave_sum(nf);
+    const unsigned wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63u) == 0u) {
+        part_u[wave] = su;
+        part_w[wave] = sw;
+        part_n[wave] = nf;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        BucketStats *st = a.stats + b;
+        st->sumsq_update += (part_u[0] + part_u[1]) + (part_u[2] + part_u[3]);
+        st->sumsq_params += (part_w[0] + part_w[1]) + (part_w[2] + part_w[3]);
+        st->nonfinite += static_cast<unsigned long long>(part_n[0]) + part_n[1] + part_n[2] + part_n[3];
+    }
 }
 
 // R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx is
@@ -752,6 +958,7 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
     s.mu = a.mu;
     s.wd = a.wd;
     s.nesterov = a.nesterov;
+    s.stats = a.stats;
 }
 
 // Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of
@@ -790,13 +997,20 @@ hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
     // next round are streamed; smaller ones are left to the cache
     const long long state_bytes = s.n * 4 * ((s.w ? 2 : 0) + (s.recv ? 1 : 0));
     const bool nts = cfg.nt_state < 0 ? state_bytes > kStateCacheBytes : cfg.nt_state != 0;
+    if (s.stats.stats) {
+        // the by-products exist for the default chunk size only
+        if (ch != 16) return hipErrorInvalidValue;
+        s.stats.n_records = (static_cast<long long>(grid) * cfg.block + 63) / 64;
+        return nts ? launch_capped(slot_kernel<BF16, FAST, true, true, 16, true>, s, bpc, cfg, grid, st)
+                   : launch_capped(slot_kernel<BF16, FAST, true, false, 16, true>, s, bpc, cfg, grid, st);
+    }
     switch (ch * 2 + (nts ? 1 : 0)) {
-    case 16: return launch_capped(slot_kernel<BF16, FAST, true, false, 8>, s, bpc, cfg, grid, st);
-    case 17: return launch_capped(slot_kernel<BF16, FAST, true, true, 8>, s, bpc, cfg, grid, st);
-    case 32: return launch_capped(slot_kernel<BF16, FAST, true, false, 16>, s, bpc, cfg, grid, st);
-    case 33: return launch_capped(slot_kernel<BF16, FAST, true, true, 16>, s, bpc, cfg, grid, st);
-    case 64: return launch_capped(slot_kernel<BF16, FAST, true, false, 32>, s, bpc, cfg, grid, st);
-    case 65: return launch_capped(slot_kernel<BF16, FAST, true, true, 32>, s, bpc, cfg, grid, st);
+    case 16: return launch_capped(slot_kernel<BF16, FAST, true, false, 8, false>, s, bpc, cfg, grid, st);
+    case 17: return launch_capped(slot_kernel<BF16, FAST, true, true, 8, false>, s, bpc, cfg, grid, st);
+    case 32: return launch_capped(slot_kernel<BF16, FAST, true, false, 16, false>, s, bpc, cfg, grid, st);
+    case 33: return launch_capped(slot_kernel<BF16, FAST, true, true, 16, false>, s, bpc, cfg, grid, st);
+    case 64: return launch_capped(slot_kernel<BF16, FAST, true, false, 32, false>, s, bpc, cfg, grid, st);
+    case 65: return launch_capped(slot_kernel<BF16, FAST, true, true, 32, false>, s, bpc, cfg, grid, st);
     default: return hipErrorInvalidValue;   // more streams per chunk exceed the scalar registers
     }
 }
@@ -904,6 +1118,30 @@ hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStr
 {
     if (a.n <= 0 || a.count <= 0) return hipSuccess;
     return bf16 ? launch_carry_t<true>(a, cfg, stream) : launch_carry_t<false>(a, cfg, stream);
+}
+
+long long slot_records(long long n, bool bf16, int block)
+{
+    const long long nvec = bf16 ? slot_nvec<true>(n) : slot_nvec<false>(n);
+    long long g = (nvec + block - 1) / block;
+    if (g < 1) g = 1;
+    return (g * block + 63) / 64;
+}
+
+hipError_t launch_stats_zero(const StatsArgs &a, hipStream_t stream)
+{
+    const int n = a.b_hi - a.b_lo;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(stats_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream)
+{
+    const int n = a.b_hi - a.b_lo;
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(stats_finish_kernel, dim3(n), dim3(256), 0, stream, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream)

@@ -104,6 +104,90 @@ def test_update_rule_variants(eb, dtype, order, wd, nesterov):
         pair.ctx.eager_set_update_rule(-1.0, False)
 
 
+def _read_stats(t):
+    """device buffer of n x 32 bytes -> list of (sumsq_update, sumsq_params, nonfinite)"""
+    raw = t.cpu().numpy().view(np.uint8).reshape(-1, 32)
+    f = raw[:, :16].copy().view(np.float64)
+    c = raw[:, 16:24].copy().view(np.uint64)
+    return [(float(f[i, 0]), float(f[i, 1]), int(c[i, 0])) for i in range(raw.shape[0])]
+
+
+@pytest.mark.parametrize("k,clip,dtype", [(2, 3000, "f32"), (3, 70001, "f32"), (5, 3100, "bf16")])
+def test_bucket_statistics(eb, k, clip, dtype):
+    """Per-bucket squared norms and non-finite counts from the fused pass (wavefront sums by
+    DPP, records, finishing kernel) against the oracle's numpy sums; tiny buckets (several
+    per wavefront), ragged ends, padding poisoned, fused, split and unfused rounds, and a
+    range call that leaves other buckets' entries alone."""
+    from oracle import eager_oracle as eo
+    cfg = shapes.scaled(shapes.config(k), clip)
+    bt = cfg.buckets
+    nb = bt.n_buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, eb.ORDER_FIXED,
+                cfg.lr, cfg.mu, seed=31)
+    stats = torch.full((nb * 4,), -1.0, dtype=torch.float64, device="cuda")
+    ws_bytes = pair.ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pair.ctx.eager_stats_attach(stats, ws, ws_bytes)
+    inside = np.zeros(bt.arena_numel, dtype=bool)
+    for o, n in zip(bt.offset, bt.numel):
+        inside[o:o + n] = True
+
+    def check(what, b0=0, b1=nb, with_w=True, w_before=None):
+        torch.cuda.synchronize()
+        got = _read_stats(stats)
+        want = eo.bucket_stats(pair.oracle_recv, w_before if with_w else None, bt.offset, bt.numel)
+        for b in range(b0, b1):
+            for j, tol in ((0, 1e-10), (1, 1e-10)):
+                assert abs(got[b][j] - want[b][j]) <= tol * max(want[b][j], 1e-300), \
+                    (what, b, j, got[b], want[b])
+            assert got[b][2] == want[b][2], (what, b, got[b], want[b])
+
+    for t in range(6):
+        plan = plan_for(eb, cfg, t)
+        G = pair.fresh_grads(t)
+        if t == 2:                                  # non-finite gradients in a few places
+            for p, i in ((0, bt.offset[0]), (1, bt.offset[nb - 1] + bt.numel[nb - 1] - 1),
+                         (0, bt.offset[nb // 2] + 1)):
+                pair.G[p][i] = float("inf")
+                G[p] = as_oracle_grad(pair.G[p])
+        # padding carries garbage that must not enter any bucket's sums
+        for p in range(cfg.P):
+            g = pair.G[p].clone()
+            g[torch.from_numpy(~inside)] = 3e4
+            pair.G[p].copy_(g)
+            G[p] = as_oracle_grad(g)
+        w_before = pair.oracle.w.copy()
+        if t == 3:
+            pair.ctx.eager_set_launch("split", 2)
+        if t == 4:
+            pair.ctx.eager_set_launch("split", 1)
+        pair.round(plan, G, want_recv=True)
+        pair.compare(exact=True, check_recv=True, what=f"stats round {t}")
+        check(f"round {t}", w_before=w_before)
+    # without an update rule the parameter norm is zero; a range call touches only its buckets
+    stats.fill_(-1.0)
+    plan = plan_for(eb, cfg, 6)
+    lo, hi = nb // 3, max(nb // 3 + 1, 2 * nb // 3)
+    pair.round(plan, pair.fresh_grads(6), lo, hi, fused=False)
+    check("range, no update rule", lo, hi, with_w=False)
+    torch.cuda.synchronize()
+    rest = _read_stats(stats)
+    assert all(rest[b] == (-1.0, -1.0, int(np.float64(-1.0).view(np.uint64)))
+               for b in list(range(lo)) + list(range(hi, nb)))
+    # the buckets now differ in their send-buffer state: a whole-range call runs as several
+    # launches, each with its own records
+    w_before = pair.oracle.w.copy()
+    pair.round(plan_for(eb, cfg, 7), pair.fresh_grads(7), want_recv=True)
+    pair.compare(exact=True, check_recv=True, what="stats, several runs")
+    check("several runs", w_before=w_before)
+    # detached: rounds run as before and leave the buffer alone
+    pair.ctx.eager_stats_attach(None, None)
+    stats.fill_(-1.0)
+    pair.round(plan_for(eb, cfg, 8), pair.fresh_grads(8))
+    pair.compare(exact=True, what="after detach")
+    assert float(stats.max()) == -1.0
+
+
 def test_quorum_rounds(eb):
     """k-of-P participation through eager_plan_quorum / eager_partial_allreduce_quorum, k
     sweeping from solo to full, on the LSTM layout; bitwise."""

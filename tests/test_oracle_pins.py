@@ -424,3 +424,29 @@ def test_plan_ties_window_quorum():
         m = eo.plan_participation(eo.MAJORITY, 5, a, 7, it, flags=eo.FLAG_STRICT_QUORUM)
         loose = eo.plan_participation(eo.MAJORITY, 5, a, 7, it)
         assert m.nap == max(3, loose.nap) and (m.mask >> m.initiator) & 1
+
+
+# ------------------------------------------------------------------ by-products
+def test_bucket_stats_closed_forms_and_library_norm():
+    """Known vectors: all ones give numel; k^2 sums; non-finite entries are counted and left
+    out; padding between buckets is ignored; agrees with numpy's own norm routine."""
+    off, num = [0, 8, 16, 16], [5, 7, 0, 9]
+    u = np.full(25, 1e30, dtype=np.float32)          # padding poisoned with large values
+    w = np.full(25, 1e30, dtype=np.float32)
+    u[0:5] = 1.0
+    u[8:15] = np.arange(1, 8)
+    u[16:25] = 2.0
+    u[17], u[20], u[24] = np.nan, np.inf, -np.inf
+    w[0:5], w[8:15], w[16:25] = 3.0, 0.5, 1.0
+    w[9] = np.nan
+    got = eo.bucket_stats(u, w, off, num)
+    assert got[0] == (5.0, 45.0, 0)
+    assert got[1] == (140.0, 6 * 0.25, 0)            # 1^2 + ... + 7^2 = 140
+    assert got[2] == (0.0, 0.0, 0)
+    assert got[3] == (6 * 4.0, 9.0, 3)
+    assert eo.bucket_stats(u, None, off, num)[0] == (5.0, 0.0, 0)
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(1000).astype(np.float32)
+    (ssu, ssw, nf), = eo.bucket_stats(x, x, [0], [1000])
+    assert nf == 0 and abs(ssu - np.linalg.norm(x.astype(np.float64)) ** 2) < 1e-9 * ssu
+    assert ssu == ssw
