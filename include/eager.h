@@ -201,8 +201,9 @@ typedef struct {
  *   workspace  device memory, 16-byte aligned, caller-owned, at least
  *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table and one
  *              32-byte record per wavefront of the round kernel there.  It must stay
- *              allocated, and must not be shared with another context that runs concurrently,
- *              while attached
+ *              allocated while attached, and is shared by all calls of this context: with
+ *              statistics attached, the calls of a context must be ordered (one stream, or
+ *              events), and no other context may use the same workspace concurrently
  *   stream     the bucket table is uploaded on this stream (asynchronously; rounds that
  *              use the statistics must be ordered after it, e.g. on the same stream)
  * Needs the compact path with its default chunk size ("compact" = 1, "chunk" = 0 or 16);

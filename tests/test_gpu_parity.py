@@ -288,6 +288,105 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
         assert torch.equal(ref, pair.w)
 
 
+def test_bucket_ranges_on_concurrent_streams(eb):
+    """Layer-wise reductions are independent (Section 3): the buckets of one round issued as
+    ranges on three streams at once, last layers first, give the bits of one whole-range
+    call."""
+    cfg = shapes.scaled(shapes.config(4), 20000)
+    bt = cfg.buckets
+    nb = bt.n_buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, "f32", eb.ORDER_FIXED, seed=17)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    cuts = [0, nb // 4, nb // 2, nb]
+    for t in range(4):
+        plan = plan_for(eb, cfg, t)
+        G = pair.fresh_grads(t)
+        torch.cuda.synchronize()                       # inputs ready before the side streams start
+        for k in (2, 1, 0):                            # backward order
+            pair.ctx.eager_partial_allreduce(plan, pair.G, pair.R, recv=pair.recv,
+                                             opt=(pair.w, pair.v, pair.lr, pair.mu),
+                                             b0=cuts[k], b1=cuts[k + 1], stream=streams[k])
+        pair.oracle.round(plan.mask, G, recv=pair.oracle_recv)
+        for st in streams:
+            st.synchronize()
+        pair.compare(exact=True, check_recv=True, what=f"three streams, t={t}")
+
+
+def test_resume_from_saved_state(eb):
+    """w, v, the send buffers, their validity masks and the round index are all the state there
+    is: a second context restored from them continues bit for bit like the first."""
+    cfg = shapes.scaled(shapes.config(2), 2500)
+    bt = cfg.buckets
+    a = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, seed=5)
+    for t in range(3):
+        a.round(plan_for(eb, cfg, t), a.fresh_grads(t))
+    torch.cuda.synchronize()
+    b = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, seed=5)
+    b.w.copy_(a.w)
+    b.v.copy_(a.v)
+    for p in range(cfg.P):
+        b.R[p].copy_(a.R[p])
+        b.oracle.R[p][:] = a.oracle.R[p]
+    b.oracle.w[:], b.oracle.v[:] = a.oracle.w, a.oracle.v
+    for k in range(bt.n_buckets):
+        b.ctx.eager_set_valid(k, a.ctx.eager_get_valid(k))
+        b.oracle.valid[k] = a.oracle.valid[k]
+    for t in range(3, 6):
+        plan = plan_for(eb, cfg, t)
+        a.round(plan, a.fresh_grads(t))
+        b.round(plan, b.fresh_grads(t))
+    a.compare(exact=True, what="uninterrupted")
+    b.compare(exact=True, what="resumed")
+    torch.cuda.synchronize()
+    assert torch.equal(a.w, b.w) and torch.equal(a.v, b.v)
+
+
+def test_round_captured_in_a_graph(eb):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset), so a round can be captured in a HIP graph.  A synchronous
+    round (everybody on time: the send buffers stay empty, so the captured launch stays
+    valid) is captured once, with the statistics attached, and replayed on new gradients,
+    with eager work and synchronisations in between; every replay is checked."""
+    from oracle import eager_oracle as eo
+    cfg = shapes.scaled(shapes.config(2), 4000)
+    bt = cfg.buckets
+    nb = bt.n_buckets
+    P = cfg.P
+    pair = Pair(eb, P, bt.offset, bt.numel, bt.arena_numel, seed=23)
+    stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+    ws_bytes = pair.ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pair.ctx.eager_stats_attach(stats, ws, ws_bytes)
+    full = eb.make_plan(eb.QUORUM, P, 0, (1 << P) - 1)
+    G = pair.fresh_grads(0)
+    pair.round(full, G, want_recv=True)                # eager warm-up round (loads the kernels)
+    pair.compare(exact=True, check_recv=True, what="eager round before capture")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        pair.ctx.eager_partial_allreduce(eb.make_plan(eb.QUORUM, P, 1, (1 << P) - 1), pair.G, pair.R,
+                                         recv=pair.recv, opt=(pair.w, pair.v, pair.lr, pair.mu),
+                                         stream=side)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for t in range(1, 5):
+        G = pair.fresh_grads(t)                        # eager copies into the captured buffers
+        w_before = pair.oracle.w.copy()
+        graph.replay()
+        pair.oracle.round(full.mask, G, recv=pair.oracle_recv)
+        pair.compare(exact=True, check_recv=True, what=f"graph replay {t}")
+        want = eo.bucket_stats(pair.oracle_recv, w_before, bt.offset, bt.numel)
+        got = _read_stats(stats)
+        for b in range(nb):
+            assert abs(got[b][0] - want[b][0]) <= 1e-10 * max(want[b][0], 1e-300), (t, b)
+            assert abs(got[b][1] - want[b][1]) <= 1e-10 * max(want[b][1], 1e-300), (t, b)
+            assert got[b][2] == want[b][2]
+        _ = (pair.w * 2).sum().item()                  # unrelated eager work and a sync
+
+
 def test_nonfinite_and_denormal_values(eb):
     """Inf/NaN gradients propagate as in the oracle; denormals are kept (no flush to
     zero), bit for bit."""
