@@ -101,21 +101,34 @@ class Workload:
             self.ctx.eager_stats_attach(self.stats, self.stats_ws, nbytes)
         self.step_no = 0
         self.q_prev = 0
+        # argument marshalling done once: pointer tables, the stream handle
+        self.Gp, self.Rp = self.ctx.pointers(self.G), self.ctx.pointers(self.R)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.mode = eb.SOLO if cfg.mode == "solo" else eb.MAJORITY
+        self.arrivals = {}
         torch.cuda.synchronize()
 
-    def plan(self, step: int):
+    def prepare(self, first: int, count: int) -> None:
+        """The seeded compute times of steps first .. first+count-1.  They are inputs of the
+        workload, like the gradients, and are produced before the timed region; deciding
+        who is on time from them (eager_plan_participation) is part of every step."""
         from workloads import times
-        cfg, eb = self.cfg, self.eb
-        t = times.compute_times(cfg.times, cfg.P, cfg.seed, step)
-        return eb.eager_plan_participation(eb.SOLO if cfg.mode == "solo" else eb.MAJORITY, t,
-                                           cfg.seed, step)
+        cfg = self.cfg
+        for s in range(first, first + count):
+            if s not in self.arrivals:
+                self.arrivals[s] = times.compute_times(cfg.times, cfg.P, cfg.seed, s)
+
+    def plan(self, step: int):
+        if step not in self.arrivals:
+            self.prepare(step, 1)
+        return self.eb.eager_plan_participation(self.mode, self.arrivals[step], self.cfg.seed, step)
 
     def step(self) -> int:
         """One step; returns its algorithmic bytes."""
         cfg = self.cfg
         plan = self.plan(self.step_no)
-        self.ctx.eager_partial_allreduce(plan, self.G, self.R, recv=None,
-                                         opt=(self.w, self.v, cfg.lr, cfg.mu))
+        self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=None,
+                                         opt=(self.w, self.v, cfg.lr, cfg.mu), stream=self.stream)
         q_now = cfg.P - plan.nap
         b = alg_bytes_per_element(cfg.P, self.gbytes, self.q_prev, q_now) * cfg.numel
         self.q_prev = q_now
@@ -131,6 +144,7 @@ def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0,
     current stream, which is the one the binding launches on)."""
     import torch
     wl = Workload(k, order, launch, stagger, clip, stats)
+    wl.prepare(0, warmup + steps)
     for _ in range(warmup):
         wl.step()
     torch.cuda.synchronize()

@@ -175,11 +175,17 @@ class Context:
             raise EagerError(st, f"{what}: {status_string(st)}: "
                                  f"{lib.eager_last_error(self._h).decode()}")
 
+    @staticmethod
+    def pointers(buffers):
+        """The pointer table of a list of device buffers, marshalled once: pass it in place
+        of the list to the partial allreduce calls of a tight loop."""
+        return (ctypes.c_void_p * max(len(buffers), 1))(*[_ptr(x) for x in buffers])
+
     def _allreduce(self, fn, what, plan, grads, resid, recv, opt, b0, b1, stream):
         b1 = self.n_buckets if b1 is None else b1
         P = len(grads)
-        g = (ctypes.c_void_p * max(P, 1))(*[_ptr(x) for x in grads])
-        r = (ctypes.c_void_p * max(len(resid), 1))(*[_ptr(x) for x in resid])
+        g = grads if isinstance(grads, ctypes.Array) else self.pointers(grads)
+        r = resid if isinstance(resid, ctypes.Array) else self.pointers(resid)
         o = None
         if opt is not None:
             params, momentum, lr, mu = opt

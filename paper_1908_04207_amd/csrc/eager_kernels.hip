@@ -980,6 +980,10 @@ hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
     if (bpc == 0) {
         bpc = (auto_waves_for_slots(s.n_slots, a.store != 0, BF16) * 64 + cfg.block - 1) / cfg.block;
         if (bpc < 1) bpc = 1;
+        // A run whose streams all fit the last-level cache is not an HBM stream: it is bound
+        // by latency, and full occupancy is fastest (1 M elements, P = 4: 8.9 against 10 us).
+        const long long run_bytes = s.n * (4ll * s.n_slots + 16);
+        if (run_bytes < kStateCacheBytes / 2) bpc = -1;
     }
     // one vector per lane, the grid covers the run ("unroll" and "max_blocks" do not apply);
     // always nontemporal (the A/B against plain loads and stores lives in the rank-chunk
