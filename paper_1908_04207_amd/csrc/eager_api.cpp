@@ -63,22 +63,25 @@ uint64_t initiator_hash(uint64_t seed, uint64_t step)
 
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
 // the reduction instead of inside it.
-bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid)
+bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid,
+               int64_t n)
 {
     if (l.split == 1) return false;
     if (l.split == 2) return true;
     // Measured on MI355X: a copy that streams one source and one destination at a time
-    // reaches 6.5 TB/s, whereas the same bytes written as many interleaved streams next to
-    // the reduction's reads cost 5-10 % of the round.  The fused pass wins only while all
-    // of its streams fit one chunk of 16 loads (one memory round trip per wavefront).  The
-    // rank-chunk kernel cannot drop the streams it does not need, and with bf16 gradients
-    // the fused pass is the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter
-    // configuration).
+    // reaches 6.7 TB/s, whereas the same bytes written as several interleaved streams next
+    // to the reduction's reads cost 5-10 % of the round (P = 8, 7 late: 6.1 fused, 6.7 split).
+    // The fused pass wins while few processes are late and all of its streams fit one chunk
+    // of 16 loads, and on short runs, where the second launch costs more than it saves
+    // (25 M elements, P = 8: 7.03 fused against 6.82 TB/s split).  The rank-chunk kernel
+    // cannot drop the streams it does not need, and with bf16 gradients the fused pass is
+    // the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter configuration).
     if (bf16 || l.compact == 0) return false;
     const uint64_t late = ~mask & low_bits(P);
     const int n_late = popcount64(late);
+    if (n_late == 0) return false;
     const int fused_streams = P + popcount64(valid);   // every G_p, every non-empty R_p
-    return n_late >= 8 || (n_late >= 1 && fused_streams > 16);
+    return fused_streams > 16 || n_late >= 8 || (n_late >= 3 && n >= (int64_t{1} << 25));
 }
 
 int check_range(eager_ctx *ctx, int b0, int b1)
@@ -176,7 +179,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
         a.dummy = static_cast<const char *>(grads[0]) + a.e0 * (ctx->bf16 ? 2 : 4);
         const uint64_t late = ~plan->mask & low_bits(P);
-        const bool split = late != 0 && use_split(ctx->launch, ctx->bf16, P, plan->mask, a.valid);
+        const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask, a.valid, a.n);
         a.gload = split ? plan->mask : low_bits(P);
         a.store = split ? 0 : late;
         if (ctx->stats) {

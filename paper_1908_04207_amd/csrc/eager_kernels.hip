@@ -962,13 +962,21 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
 }
 
 // Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of
-// late gradients in the same pass few wavefronts are best once there are many streams
-// (bf16 gradients, whose loads carry half the bytes, like a few more); a pass that only
-// reads (apart from w and v) likes more.
-int auto_waves_for_slots(int n_slots, bool has_stores, bool bf16)
+// late gradients in the same pass few wavefronts are best once there are many streams; a
+// pass that only reads (apart from w and v) likes more while one chunk holds all streams.
+// What counts is the bytes in flight per CU: a bf16 stream carries half as many per load, so
+// the count grows with the share of bf16 streams (all bf16: twice as many wavefronts).
+int auto_waves_for_slots(const SlotArgs &s, bool has_stores)
 {
-    if (has_stores) return n_slots <= 16 ? 8 : bf16 ? 7 : 5;   // one chunk of 16 or several
-    return n_slots <= 20 ? 10 : 5;
+    const int n = s.n_slots;
+    const int base = has_stores ? (n <= 16 ? 8 : 5) : (n <= 20 ? 10 : 5);
+    const int n_bf = __builtin_popcountll(s.bf[0]) + __builtin_popcountll(s.bf[1]);
+    // (one chunk with stores: the stores are full-width fp32 whatever the gradient type, and
+    // 8 stays the best count - P = 8, bf16, majority: 6.46 against 6.23 TB/s with 12)
+    if (n_bf == 0 || n == 0 || (has_stores && n <= 16)) return base;
+    // base / (1 - share/2), rounded
+    const int waves = (2 * base * n + (2 * n - n_bf) / 2) / (2 * n - n_bf);
+    return waves > 16 ? 16 : waves;
 }
 
 template <bool BF16, bool FAST>
@@ -978,7 +986,7 @@ hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
     build_slots(a, s);
     int bpc = cfg.blocks_per_cu;
     if (bpc == 0) {
-        bpc = (auto_waves_for_slots(s.n_slots, a.store != 0, BF16) * 64 + cfg.block - 1) / cfg.block;
+        bpc = (auto_waves_for_slots(s, a.store != 0) * 64 + cfg.block - 1) / cfg.block;
         if (bpc < 1) bpc = 1;
         // A run whose streams all fit the last-level cache is not an HBM stream: it is bound
         // by latency, and full occupancy is fastest (1 M elements, P = 4: 8.9 against 10 us).
