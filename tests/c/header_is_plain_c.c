@@ -1,0 +1,46 @@
+/* The public header must be usable from plain C: this file includes it in a C99 translation
+ * unit, takes the address of every entry point with its declared type, and checks the layout
+ * of the structures that cross the boundary.  Compiled (not run) by tests/test_host_library.py. */
+#include "eager.h"
+
+#include <stddef.h>
+
+typedef char static_check_plan[(sizeof(eager_plan) == 32 && offsetof(eager_plan, mask) == 16) ? 1 : -1];
+typedef char static_check_stats[(sizeof(eager_bucket_stats) == 32) ? 1 : -1];
+typedef char static_check_opt[(offsetof(eager_opt, lr) == 2 * sizeof(void *)) ? 1 : -1];
+
+int (*const p_create)(eager_ctx **, int, int, const int64_t *, const int64_t *, int, int) = eager_create;
+int (*const p_destroy)(eager_ctx *) = eager_destroy;
+const char *(*const p_last_error)(const eager_ctx *) = eager_last_error;
+const char *(*const p_status_string)(int) = eager_status_string;
+int (*const p_plan)(int, int, const double *, uint64_t, uint64_t, double, uint32_t, eager_plan *) =
+    eager_plan_participation;
+int (*const p_plan_quorum)(int, const double *, int, uint64_t, double, eager_plan *) = eager_plan_quorum;
+int (*const p_solo)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
+                    float *, const eager_opt *, void *) = eager_partial_allreduce_solo;
+int (*const p_majority)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
+                        float *, const eager_opt *, void *) = eager_partial_allreduce_majority;
+int (*const p_quorum)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
+                      float *, const eager_opt *, void *) = eager_partial_allreduce_quorum;
+int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
+int (*const p_rule)(eager_ctx *, float, int) = eager_set_update_rule;
+int (*const p_stats_bytes)(const eager_ctx *, int64_t *) = eager_stats_workspace_bytes;
+int (*const p_stats_attach)(eager_ctx *, eager_bucket_stats *, void *, int64_t, void *) = eager_stats_attach;
+int (*const p_get_valid)(const eager_ctx *, int, uint64_t *) = eager_get_valid;
+int (*const p_set_valid)(eager_ctx *, int, uint64_t) = eager_set_valid;
+int (*const p_set_launch)(eager_ctx *, const char *, int) = eager_set_launch;
+int (*const p_calib_copy)(void *, const void *, int64_t, void *) = eager_calib_copy;
+int (*const p_calib_read)(const void *, int64_t, float *, void *) = eager_calib_read;
+
+/* host-only calls can run without a GPU: plan one round of each kind */
+int main(void)
+{
+    const double arrival[4] = {3.0, 1.0, 2.0, 1.0};
+    eager_plan plan;
+    if (eager_plan_participation(EAGER_SOLO, 4, arrival, 1u, 0u, 0.0, 0u, &plan) != EAGER_OK) return 1;
+    if (plan.initiator != 1 || plan.mask != 0xAu || plan.nap != 2) return 2;      /* tie: ranks 1 and 3 */
+    if (eager_plan_quorum(4, arrival, 3, 0u, 0.0, &plan) != EAGER_OK) return 3;
+    if (plan.initiator != 2 || plan.mask != 0xEu || plan.mode != EAGER_QUORUM) return 4;
+    if (eager_plan_quorum(4, arrival, 5, 0u, 0.0, &plan) != EAGER_EINVAL) return 5;
+    return 0;
+}

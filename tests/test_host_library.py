@@ -25,6 +25,20 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c_and_host_calls_run_from_c(tmp_path):
+    """include/eager.h in a C99 translation unit (gcc, pedantic), every entry point with its
+    declared type, structure layouts; the program links against the library and runs the
+    host-only planning calls (no GPU needed)."""
+    import subprocess
+    exe = tmp_path / "header_is_plain_c"
+    lib_dir = os.path.dirname(eb.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                           "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "c", "header_is_plain_c.c"),
+                           "-o", str(exe), "-L", lib_dir, "-leager", "-Wl,-rpath," + lib_dir])
+    assert subprocess.run([str(exe)]).returncode == 0
+
+
 def test_plan_matches_oracle_on_all_configs():
     for k in range(1, 6):
         cfg = shapes.config(k)

@@ -450,3 +450,21 @@ def test_bucket_stats_closed_forms_and_library_norm():
     (ssu, ssw, nf), = eo.bucket_stats(x, x, [0], [1000])
     assert nf == 0 and abs(ssu - np.linalg.norm(x.astype(np.float64)) ** 2) < 1e-9 * ssu
     assert ssu == ssw
+
+
+# ------------------------------------------------------------------ memory safety of the C file
+def test_c_oracle_under_address_and_ub_sanitizers(tmp_path):
+    """The C oracle driven from C under AddressSanitizer and UndefinedBehaviorSanitizer: every
+    mask sequence over three rounds plus a flush, ragged sizes including 0, fp32 and bf16,
+    threaded and scalar; conservation checked exactly on integer-valued data."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "oracle_sanitized"
+    subprocess.check_call(["gcc", "-std=c11", "-O1", "-g", "-ffp-contract=off", "-fopenmp",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-Wall", "-Wextra",
+                           os.path.join(root, "tests", "c", "oracle_sanitized.c"),
+                           os.path.join(root, "oracle", "eager_oracle.c"), "-o", str(exe), "-lm"])
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", r.stderr[-2000:]
