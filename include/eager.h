@@ -184,8 +184,8 @@ int eager_set_update_rule(eager_ctx *ctx, float weight_decay, int nesterov);
  *                 result of the round (Algorithm 2 line 6); squares and sums in fp64
  *   sumsq_params  the same over the parameters w_i BEFORE the update (0 without opt)
  *   nonfinite     number of elements whose u_i is NaN or infinite
- * Sums are reproducible from run to run except in the wavefronts that hold a bucket boundary
- * (their lanes add atomically, in arbitrary order); compare with a tolerance.
+ * The sums are formed in a fixed order (no atomics): reproducible bit for bit from run to run
+ * for a given launch shape; against another implementation compare with a tolerance.
  */
 typedef struct {
     double   sumsq_update;
@@ -199,15 +199,15 @@ typedef struct {
  * writes stats[b] for each bucket b it covers (overwritten by every call).
  *   stats      device array of n_buckets entries, 16-byte aligned, caller-owned; NULL detaches
  *   workspace  device memory, 16-byte aligned, caller-owned, at least
- *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table and one
- *              32-byte record per wavefront of the round kernel there.  It must stay
+ *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table, one
+ *              32-byte record per wavefront of the round kernel and a few per bucket there.  It must stay
  *              allocated while attached, and is shared by all calls of this context: with
  *              statistics attached, the calls of a context must be ordered (one stream, or
  *              events), and no other context may use the same workspace concurrently
  *   stream     the bucket table is uploaded on this stream (asynchronously; rounds that
  *              use the statistics must be ordered after it, e.g. on the same stream)
  * Needs the compact path with its default chunk size ("compact" = 1, "chunk" = 0 or 16);
- * otherwise the next round fails with ESTATE.  Two extra small kernels run per call.
+ * otherwise the next round fails with ESTATE.  One extra small kernel runs per launch.
  * Errors: EINVAL (NULL ctx, workspace too small or misaligned), ENOMEM, EDEVICE.
  */
 int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes);

@@ -61,6 +61,12 @@ uint64_t initiator_hash(uint64_t seed, uint64_t step)
     return z ^ (z >> 31);
 }
 
+// wavefronts a round kernel may be launched with over the whole arena, whatever the block size
+int64_t max_records(const eager_ctx *ctx)
+{
+    const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
+    return span / 256 + 8;
+}
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
 // the reduction instead of inside it.
 bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid,
@@ -158,12 +164,8 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.stats.stats = ctx->stats;
         a.stats.records = reinterpret_cast<eager::StatsRecord *>(
             ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
+        a.stats.lane_records = a.stats.records + max_records(ctx);
         a.stats.n_buckets = ctx->n_buckets;
-        a.stats.b_lo = b0;
-        a.stats.b_hi = b1;
-        hipError_t he = eager::launch_stats_zero(a.stats, static_cast<hipStream_t>(stream));
-        if (he != hipSuccess)
-            return fail(ctx, EAGER_EDEVICE, "statistics kernel launch failed: %s", hipGetErrorString(he));
     }
 
     // Consecutive buckets whose send buffers are in the same state form one run = one
@@ -187,6 +189,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
             a.stats.b_lo = b;
             a.stats.b_hi = e;
             a.stats.n_records = eager::slot_records(a.n, ctx->bf16, ctx->launch.block);
+            a.stats.tail_count = eager::slot_tail(a.n, ctx->bf16);
         }
         hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
                                             static_cast<hipStream_t>(stream));
@@ -423,20 +426,13 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask)
     return EAGER_OK;
 }
 
-namespace {
-// wavefronts a round kernel may be launched with over the whole arena, whatever the block size
-int64_t max_records(const eager_ctx *ctx)
-{
-    const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
-    return span / 256 + 8;
-}
-}  // namespace
-
 int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes)
 {
     if (!ctx || !bytes) return EAGER_EINVAL;
+    // bucket table, one record per wavefront, (n_buckets + 1) blocks of 64 lane records
     *bytes = static_cast<int64_t>(ctx->n_buckets) * 16 +
-             max_records(ctx) * static_cast<int64_t>(sizeof(eager::StatsRecord));
+             (max_records(ctx) + (static_cast<int64_t>(ctx->n_buckets) + 1) * 64) *
+                 static_cast<int64_t>(sizeof(eager::StatsRecord));
     return EAGER_OK;
 }
 

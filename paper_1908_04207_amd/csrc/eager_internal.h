@@ -20,8 +20,10 @@ struct BucketStats {
 };
 
 // What one wavefront of the round kernel leaves for the finishing kernel: the sums over its
-// 256 elements if they all lie in one bucket (bucket >= 0), else bucket = -1 (then its lanes
-// have added to the bucket totals themselves).
+// 256 elements if they all lie in one bucket (bucket >= 0); bucket = -1 if they lie in several
+// (then every lane has left a record of its own in block `nf` of the lane records); bucket =
+// -2 if the wavefront holds no element.  Lane records and the records of the ragged tail
+// (at most 7 single elements, in the block after the last bucket's) have the same layout.
 struct StatsRecord {
     double ssu, ssw;
     int bucket;
@@ -33,6 +35,8 @@ struct StatsArgs {
     const long long *table;      // device: start, end of every bucket (2 per bucket)
     BucketStats *stats;          // device: one per bucket
     StatsRecord *records;        // device: one per wavefront of the round kernel
+    StatsRecord *lane_records;   // device: (n_buckets + 1) blocks of 64
+    int tail_count;              // elements of the run's ragged tail (0..7)
     long long e0;                // first element of the run
     long long n_records;         // wavefronts the round kernel was launched with
     int b_lo, b_hi;              // buckets of the run
@@ -136,9 +140,9 @@ struct Launch {
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
 hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream);
-hipError_t launch_stats_zero(const StatsArgs &a, hipStream_t stream);
 hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
 long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch
+int slot_tail(long long n, bool bf16);                       // elements of its ragged tail
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

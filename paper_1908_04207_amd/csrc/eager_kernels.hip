@@ -351,9 +351,10 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs)
 // parameters, count of non-finite elements.  They are reductions ACROSS elements, the one
 // place on this path where cross-lane work belongs: a lane sums its 4 elements, the 64 lanes
 // of a wavefront are combined with DPP moves inside rows of 16 lanes and lane reads across
-// the 4 rows, and one lane writes one record per wavefront (no atomics on the common path,
-// and a fixed tree: the result is reproducible).  A finishing kernel adds the records of a
-// bucket, combining the wavefronts of its workgroup through LDS.
+// the 4 rows, and one lane writes one record per wavefront.  A wavefront whose elements lie in
+// several buckets leaves one record per lane instead.  No atomics anywhere and fixed trees:
+// the result is reproducible bit for bit.  A finishing kernel adds the records of a bucket,
+// combining the wavefronts of its workgroup through LDS.
 struct LaneStats {
     double ssu, ssw;   // squares of the update / of the old parameters
     unsigned nf;       // non-finite elements of the update
@@ -426,34 +427,25 @@ __device__ __forceinline__ void stats_add(LaneStats &ls, float u, float w_old, b
         ls.ssw += static_cast<double>(w_old) * static_cast<double>(w_old);
 }
 
-__device__ __forceinline__ void stats_atomic(BucketStats *st, const LaneStats &ls)
-{
-    if (ls.bucket < 0) return;
-    BucketStats *b = st + ls.bucket;
-    if (ls.ssu != 0.0)
-        __hip_atomic_fetch_add(&b->sumsq_update, ls.ssu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (ls.ssw != 0.0)
-        __hip_atomic_fetch_add(&b->sumsq_params, ls.ssw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (ls.nf != 0u)
-        __hip_atomic_fetch_add(&b->nonfinite, static_cast<unsigned long long>(ls.nf),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// Called by every lane of a wavefront (all active).  One record per wavefront; a wavefront
-// whose elements lie in several buckets (or that holds a ragged end) adds per lane instead.
-__device__ __forceinline__ void stats_commit(BucketStats *stats, StatsRecord *records,
+// Called by every lane of a wavefront (all active).  The lanes that hold elements are a
+// prefix of the wavefront and buckets ascend with the lane, so a mixed wavefront is the only
+// one whose first lane lies in bucket b0 while a later lane does not: block b0 of the lane
+// records is its own.
+__device__ __forceinline__ void stats_commit(StatsRecord *records, StatsRecord *lane_records,
                                              const LaneStats &ls, long long wave_index)
 {
     const int b0 = __builtin_amdgcn_readfirstlane(ls.bucket);
     const bool mixed = __builtin_amdgcn_ballot_w64(ls.bucket != b0) != 0ull;
-    StatsRecord rec = {0.0, 0.0, -1, 0u, 0};
-    if (!mixed && b0 >= 0) {
+    StatsRecord rec = {0.0, 0.0, b0 >= 0 ? b0 : -2, 0u, 0};
+    if (mixed) {
+        const StatsRecord mine = {ls.ssu, ls.ssw, ls.bucket, ls.nf, 0};
+        lane_records[static_cast<long long>(b0) * 64 + (threadIdx.x & 63u)] = mine;
+        rec.bucket = -1;
+        rec.nf = static_cast<unsigned>(b0);
+    } else if (b0 >= 0) {
         rec.ssu = wave_sum(ls.ssu);
         rec.ssw = wave_sum(ls.ssw);
         rec.nf = wave_sum(ls.nf);
-        rec.bucket = b0;
-    } else if (mixed) {
-        stats_atomic(stats, ls);
     }
     if ((threadIdx.x & 63u) == 0u) records[wave_index] = rec;
 }
@@ -643,13 +635,14 @@ __device__ __forceinline__ void slot_scalar(KSlotArgs &a, long long i)
     const float avg = s * a.inv_P;
     if (a.recv) a.recv[i] = avg;
     if (STATS) {
-        // a handful of elements per launch: straight to the bucket totals
+        // a handful of single elements per launch: one record each, in the block after the
+        // last bucket's
         const long long *tbl = a.stats.table;
         LaneStats ls = {0.0, 0.0, 0u, find_bucket(tbl, a.stats.n_buckets, i)};
-        if (i < tbl[2 * ls.bucket + 1]) {
-            stats_add(ls, avg, a.w ? a.w[i] : 0.0f, a.w != nullptr);
-            stats_atomic(a.stats.stats, ls);
-        }
+        if (i < tbl[2 * ls.bucket + 1]) stats_add(ls, avg, a.w ? a.w[i] : 0.0f, a.w != nullptr);
+        else ls.bucket = -2;                                   // padding
+        const StatsRecord mine = {ls.ssu, ls.ssw, ls.bucket, ls.nf, 0};
+        a.stats.lane_records[static_cast<long long>(a.stats.n_buckets) * 64 + threadIdx.x] = mine;
     }
     if (a.w) {
         const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
@@ -706,27 +699,16 @@ __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
         }
         slot_vectors<BF16, FAST, NT, NTS, 1, CH, STATS>(a, lv, n_valid, ls);
     }
-    if (STATS) stats_commit(a.stats.stats, a.stats.records, ls, vi >> 6);
+    if (STATS) stats_commit(a.stats.records, a.stats.lane_records, ls, vi >> 6);
     const long long rem = a.n - nvec * 4;
     if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem)
         slot_scalar<BF16, STATS>(a, a.e0 + nvec * 4 + threadIdx.x);
 }
 
-// stats[b] = 0 for the buckets a call covers (a kernel, not a memset, so that a caller may
-// capture the call in a graph)
-__global__ __launch_bounds__(256) void stats_zero_kernel(const StatsArgs a)
-{
-    const int b = a.b_lo + static_cast<int>(blockIdx.x * blockDim.x + threadIdx.x);
-    if (b < a.b_hi) {
-        const BucketStats z = {0.0, 0.0, 0ull, 0ull};
-        a.stats[b] = z;
-    }
-}
-
 // One workgroup per bucket of the run: adds the records of the wavefronts whose 256 elements
-// lie in the bucket (they are consecutive), wavefront sums by DPP, the 4 wavefronts of the
-// workgroup through LDS, then one thread adds the result to what lanes of mixed wavefronts
-// have already put there.
+// touch the bucket (they are consecutive) - a uniform wavefront's sums, or a mixed wavefront's
+// lane records of this bucket - and the records of the ragged tail; wavefront sums by DPP, the
+// 4 wavefronts of the workgroup through LDS; one thread writes the bucket's totals.
 __global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
 {
     __shared__ double part_u[4], part_w[4];
@@ -737,12 +719,47 @@ __global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
     if (w1 > a.n_records) w1 = a.n_records;
     double su = 0.0, sw = 0.0;
     unsigned nf = 0u;
-    for (long long w = w0 + threadIdx.x; w < w1; w += blockDim.x) {
-        const StatsRecord r = a.records[w];
-        if (r.bucket == b) {
-            su += r.ssu;
-            sw += r.ssw;
-            nf += r.nf;
+    // a large bucket has thousands of records for the one workgroup: 8 independent loads per
+    // thread are in flight together
+    constexpr int K = 8;
+    for (long long wb = w0 + threadIdx.x; wb < w1; wb += static_cast<long long>(blockDim.x) * K) {
+        StatsRecord r[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const long long w = wb + static_cast<long long>(k) * blockDim.x;
+            if (w < w1) r[k] = a.records[w];
+            else r[k].bucket = -2;
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            if (r[k].bucket == b) {
+                su += r[k].ssu;
+                sw += r[k].ssw;
+                nf += r[k].nf;
+            }
+        }
+    }
+    // Only the first and the last wavefront of the bucket can be mixed: wavefront 0 of this
+    // workgroup takes the lane records of the first, wavefront 1 those of the last, one lane
+    // each; wavefront 2 takes the ragged tail.
+    const unsigned which = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    if (which < 2 && w1 > w0 && (which == 0 || w1 - 1 != w0)) {
+        const StatsRecord r = a.records[which == 0 ? w0 : w1 - 1];
+        if (r.bucket == -1) {
+            const StatsRecord lr = a.lane_records[static_cast<long long>(r.nf) * 64 + lane];
+            if (lr.bucket == b) {
+                su += lr.ssu;
+                sw += lr.ssw;
+                nf += lr.nf;
+            }
+        }
+    }
+    if (which == 2 && static_cast<int>(lane) < a.tail_count) {
+        const StatsRecord tr = a.lane_records[static_cast<long long>(a.n_buckets) * 64 + lane];
+        if (tr.bucket == b) {
+            su += tr.ssu;
+            sw += tr.ssw;
+            nf += tr.nf;
         }
     }
     su = wave_sum(su);
@@ -756,10 +773,12 @@ __global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        BucketStats *st = a.stats + b;
-        st->sumsq_update += (part_u[0] + part_u[1]) + (part_u[2] + part_u[3]);
-        st->sumsq_params += (part_w[0] + part_w[1]) + (part_w[2] + part_w[3]);
-        st->nonfinite += static_cast<unsigned long long>(part_n[0]) + part_n[1] + part_n[2] + part_n[3];
+        BucketStats out;
+        out.sumsq_update = (part_u[0] + part_u[1]) + (part_u[2] + part_u[3]);
+        out.sumsq_params = (part_w[0] + part_w[1]) + (part_w[2] + part_w[3]);
+        out.nonfinite = static_cast<unsigned long long>(part_n[0]) + part_n[1] + part_n[2] + part_n[3];
+        out.reserved = 0ull;
+        a.stats[b] = out;
     }
 }
 
@@ -1140,12 +1159,9 @@ long long slot_records(long long n, bool bf16, int block)
     return (g * block + 63) / 64;
 }
 
-hipError_t launch_stats_zero(const StatsArgs &a, hipStream_t stream)
+int slot_tail(long long n, bool bf16)
 {
-    const int n = a.b_hi - a.b_lo;
-    if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(stats_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, a);
-    return hipGetLastError();
+    return static_cast<int>(n - (bf16 ? slot_nvec<true>(n) : slot_nvec<false>(n)) * 4);
 }
 
 hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream)

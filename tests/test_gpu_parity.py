@@ -188,6 +188,27 @@ def test_bucket_statistics(eb, k, clip, dtype):
     assert float(stats.max()) == -1.0
 
 
+def test_bucket_statistics_are_reproducible(eb):
+    """No atomics, fixed trees: two runs of the same rounds give the same bits."""
+    cfg = shapes.scaled(shapes.config(2), 5000)
+    bt = cfg.buckets
+    outs = []
+    for rep in range(2):
+        pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, seed=41)
+        stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device="cuda")
+        nbytes = pair.ctx.eager_stats_workspace_bytes()
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        pair.ctx.eager_stats_attach(stats, ws, nbytes)
+        per_round = []
+        for t in range(3):
+            pair.round(plan_for(eb, cfg, t), pair.fresh_grads(t))
+            torch.cuda.synchronize()
+            per_round.append(stats.clone())
+        outs.append(per_round)
+    for x, y in zip(*outs):
+        assert torch.equal(x.view(torch.int64), y.view(torch.int64))
+
+
 def test_quorum_rounds(eb):
     """k-of-P participation through eager_plan_quorum / eager_partial_allreduce_quorum, k
     sweeping from solo to full, on the LSTM layout; bitwise."""
