@@ -93,6 +93,43 @@ def test_quorum_plan_matches_oracle_and_spans_solo_to_full():
         assert e.value.status == eb.EINVAL
 
 
+def test_microbenchmark_latency_shape_and_nap():
+    """The paper's microbenchmark (Section 7.1, Fig. 9): 32 processes skewed linearly from 1
+    to 32 ms, 64 iterations.  With the library's planner and the simplest latency model - a
+    process waits from its arrival until the initiator triggers the round, then the
+    collective itself takes t_c - the waits have closed forms, and the reported ratios
+    (53.32x for solo, 2.46x for majority over the full allreduce) fall where those forms put
+    them for a collective of a few hundred microseconds.  NAP: exactly 1 for solo, rank of
+    the initiator + 1 for majority, about half the processes on average."""
+    P, iters = 32, 64
+    arrival = [float(p + 1) for p in range(P)]
+
+    def mean_wait(plans):
+        return sum(sum(max(0.0, arrival[pl.initiator] - a) for a in arrival) / P
+                   for pl in plans) / len(plans)
+
+    solo = [eb.eager_plan_participation(eb.SOLO, arrival, 3, t) for t in range(iters)]
+    full = [eb.eager_plan_quorum(arrival, P, t) for t in range(iters)]
+    assert all(pl.nap == 1 and pl.initiator == 0 for pl in solo)
+    assert all(pl.nap == P and pl.initiator == P - 1 for pl in full)
+    assert mean_wait(solo) == 0.0
+    assert mean_wait(full) == (P - 1) / 2.0                       # mean of 31, 30, ..., 0 ms
+    naps, waits = [], []
+    for seed in range(200):
+        maj = [eb.eager_plan_participation(eb.MAJORITY, arrival, seed, t) for t in range(iters)]
+        assert all(pl.nap == pl.initiator + 1 for pl in maj)
+        naps.append(sum(pl.nap for pl in maj) / iters)
+        waits.append(mean_wait(maj))
+    # initiator uniform over the ranks: E[NAP] = (P+1)/2, E[wait] = (P^2 - 1) / (6 P) ms
+    assert abs(np.mean(naps) - (P + 1) / 2.0) < 0.15
+    assert abs(np.mean(waits) - (P * P - 1) / (6.0 * P)) < 0.1
+    t_c = 0.3                                                     # ms, a small-message allreduce
+    lat_full, lat_solo, lat_maj = (P - 1) / 2.0 + t_c, t_c, float(np.mean(waits)) + t_c
+    assert 40 < lat_full / lat_solo < 70                          # the paper reports 53.32x
+    assert 2.0 < lat_full / lat_maj < 3.5                         # the paper reports 2.46x
+    assert lat_solo < lat_maj < lat_full
+
+
 def test_plan_rejects_bad_arguments():
     for bad in (lambda: eb.eager_plan_participation(7, [1.0], 0, 0),
                 lambda: eb.eager_plan_participation(eb.SOLO, [], 0, 0),
