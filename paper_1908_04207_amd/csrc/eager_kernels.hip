@@ -5,18 +5,25 @@
 // The path is a pure stream: per element <= 2P adds, one multiply and two FMAs against
 // >= 4P bytes, so HBM bandwidth is the only roofline that matters and there is no
 // contraction for the matrix cores.  Design for CDNA4:
-//   * a thread owns one 16-byte vector of each gradient stream (4 fp32 or 8 bf16
-//     elements), so a 64-lane wavefront reads 1 KiB contiguous per stream per load;
-//   * the P gradient loads and the loads of the non-empty send buffers of a chunk of
-//     ranks are all issued before the first add, which keeps (2*CH+2) x 16 B per lane in
-//     flight - that, not occupancy, is what covers HBM latency;
-//   * which streams are read or written is decided from two 64-bit masks that live in
-//     scalar registers: every branch is uniform, empty send buffers cost no bytes, the
-//     send buffer of an on-time process is "cleared" by a flag on the host, not by
-//     writing zeros;
-//   * the accumulator stays in fp32 registers; in fixed-order mode contributions are
-//     added in ascending rank order from +0.0f with contraction off, so the result is
-//     defined bit for bit; fast mode sums a chunk as a tree and lets the compiler fuse.
+//   * slot_kernel (the default): the host compacts the round into a list of streams that
+//     must be read, in summation order; a lane owns 4 consecutive elements of every stream,
+//     so a 64-lane wavefront reads or writes one contiguous KiB per fp32 stream and
+//     instruction; the loads of a chunk of 16 streams are all issued before the first add,
+//     which keeps 16-18 x 16 B per lane in flight - that, together with a deliberately
+//     capped occupancy, is what suits HBM with mixed reads and writes;
+//   * which streams exist and what is done with each is decided on the host and applied in
+//     the kernel with scalar bit masks: no branch around a load, empty send buffers cost
+//     no bytes, the send buffer of an on-time process is "cleared" by a flag on the host,
+//     not by writing zeros;
+//   * the accumulator stays in fp32 registers; in fixed-order mode contributions are added
+//     in ascending rank order from +0.0f with contraction off, so the result is defined
+//     bit for bit; fast mode keeps two partial sums and lets the compiler fuse;
+//   * carry_kernel: the send-buffer rewrite of late processes as a plain pair-by-pair
+//     copy, when a round is split;
+//   * round_kernel: the earlier form (fixed chunks of ranks, stand-in loads for absent
+//     streams), kept for comparison;
+//   * optional per-bucket norms as by-products: DPP sums inside wavefronts, LDS across
+//     them (stats_*).
 #include "eager_internal.h"
 
 #include <mutex>
