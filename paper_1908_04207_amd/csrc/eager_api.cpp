@@ -518,6 +518,9 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
     } else if (!std::strcmp(key, "nt_state")) {
         if (value < -1 || value > 1) return fail(ctx, EAGER_EINVAL, "nt_state must be -1, 0 or 1");
         ctx->launch.nt_state = value;
+    } else if (!std::strcmp(key, "xcd_map")) {
+        if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "xcd_map must be 0 or 1");
+        ctx->launch.xcd_map = value;
     } else if (!std::strcmp(key, "carry_block")) {
         if (value != 64 && value != 128 && value != 256)
             return fail(ctx, EAGER_EINVAL, "carry_block must be 64, 128 or 256");

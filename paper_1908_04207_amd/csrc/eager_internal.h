@@ -95,6 +95,7 @@ struct SlotArgs {
     long long e0, n;
     float inv_P, neg_lr, mu, wd;
     int nesterov;
+    int xcd_map;                       // 1: every XCD takes a contiguous eighth of the run
     StatsArgs stats;
 };
 
@@ -132,6 +133,7 @@ struct Launch {
                            // kernel followed by a carry (copy) kernel
     int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
     int nt_state = -1;     // w, v, recv nontemporal: -1 chosen from their size, 0 no, 1 yes
+    int xcd_map = 0;       // slot kernel: 1 = contiguous eighth of the run per XCD
     int carry_block = 64;  // carry kernel: threads per workgroup
     int carry_vec = 1;     // carry kernel: lane-vectors per thread and iteration (1, 2, 4)
     int carry_blocks_per_cu = -1;  // carry kernel: -1 no cap, else max workgroups per CU

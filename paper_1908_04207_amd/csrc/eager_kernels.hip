@@ -677,7 +677,14 @@ __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
 {
     KSlotArgs &a = kernarg<SlotArgs>();
     const long long nvec = slot_nvec<BF16>(a.n);
-    const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    // Workgroups are dealt to the 8 XCDs round robin.  xcd_map = 1 gives every XCD one
+    // contiguous eighth of the run instead of every eighth tile (a launch option, for A/B).
+    unsigned bid = blockIdx.x;
+    if (a.xcd_map) {
+        const unsigned per = gridDim.x / 8u;
+        if (bid < per * 8u) bid = (bid % 8u) * per + bid / 8u;
+    }
+    const long long vi = static_cast<long long>(bid) * blockDim.x + threadIdx.x;
     LaneStats ls = {0.0, 0.0, 0u, -1};
     int n_valid = 0;
     int wave_bucket = 0;
@@ -985,6 +992,7 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
     s.wd = a.wd;
     s.nesterov = a.nesterov;
     s.stats = a.stats;
+    s.xcd_map = 0;
 }
 
 // Resident 64-lane wavefronts per CU for the slot kernel (measured optima): with stores of
@@ -1035,6 +1043,7 @@ hipError_t launch_slots(const RoundArgs &a, const Launch &cfg, hipStream_t st)
     // next round are streamed; smaller ones are left to the cache
     const long long state_bytes = s.n * 4 * ((s.w ? 2 : 0) + (s.recv ? 1 : 0));
     const bool nts = cfg.nt_state < 0 ? state_bytes > kStateCacheBytes : cfg.nt_state != 0;
+    s.xcd_map = cfg.xcd_map;
     if (s.stats.stats) {
         // the by-products exist for the default chunk size only
         if (ch != 16) return hipErrorInvalidValue;

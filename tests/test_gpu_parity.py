@@ -293,7 +293,8 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
         dict(block=256, unroll=2, max_blocks=7, nontemporal=0, chunk=8, blocks_per_cu=3, split=0,
              compact=1, carry_block=128, carry_vec=2),
         dict(block=64, unroll=2, max_blocks=0, nontemporal=1, chunk=8, blocks_per_cu=-1, split=2,
-             compact=1, carry_vec=2, carry_blocks_per_cu=32),
+             compact=1, carry_vec=2, carry_blocks_per_cu=32, xcd_map=1),
+        dict(block=128, chunk=32, split=1, compact=1, xcd_map=1),
         dict(block=64, unroll=1, max_blocks=2, nontemporal=1, chunk=32 if dtype == "f32" else 16,
              blocks_per_cu=5, split=2, compact=0, carry_block=64, carry_vec=4)]
     for launch in shapes_:
