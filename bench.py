@@ -126,7 +126,7 @@ class Workload:
     def step(self) -> int:
         """One step; returns its algorithmic bytes."""
         cfg = self.cfg
-        plan = self.plan(self.step_no)
+        plan = self.last_plan = self.plan(self.step_no)
         self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=None,
                                          opt=(self.w, self.v, cfg.lr, cfg.mu), stream=self.stream)
         q_now = cfg.P - plan.nap
@@ -158,6 +158,25 @@ def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0,
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return wl, wall, nbytes, e0.elapsed_time(e1) * 1e-3
+
+
+def trace_steps(wl: "Workload", steps: int, path: str) -> None:
+    """Per-step log (JSON lines) of a separate, untimed pass: participation of the round,
+    algorithmic bytes, GPU time of the step between two HIP events, GB/s."""
+    import torch
+    with open(path, "w") as f:
+        for _ in range(steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            b = wl.step()
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            pl = wl.last_plan
+            f.write(json.dumps({"step": wl.step_no - 1, "nap": pl.nap, "initiator": pl.initiator,
+                                "mask": f"{pl.mask:#x}", "alg_bytes": b,
+                                "gpu_us": round(ms * 1e3, 2),
+                                "GBps": round(b / (ms * 1e-3) / 1e9, 1)}) + "\n")
 
 
 def copy_ceiling_gbs() -> dict:
@@ -256,6 +275,9 @@ def main() -> int:
     ap.add_argument("--clip", type=int, default=0,
                     help="clip every tensor to this many elements (a reduced layout of the same "
                          "configuration, for counter runs the profiler cannot take at full size)")
+    ap.add_argument("--trace", default="", metavar="FILE",
+                    help="after the timed run, log this many more steps one by one to FILE "
+                         "(JSON lines: NAP, initiator, mask, bytes, GPU microseconds)")
     ap.add_argument("--stats", action="store_true",
                     help="also compute the per-bucket norms in every round (eager_stats_attach)")
     a = ap.parse_args()
@@ -298,6 +320,8 @@ def main() -> int:
                      "avg_kernel_ms": round(kern_s / a.steps * 1e3, 5)},
         "paper_context": PAPER_CONTEXT,
     }
+    if a.trace:
+        trace_steps(wl, min(a.steps, 64), a.trace)
     if not a.no_ceiling:
         c = copy_ceiling_gbs()
         out["measured_ceiling_GBs"] = {"copy_read_plus_write": round(c["copy"], 1),
