@@ -4,7 +4,8 @@ one MI355X, on synthetic gradients shaped like the paper's workloads.
 
 A step = plan participation from that step's seeded compute times (host) + one fused
 round over every bucket of the model (device).  Inputs are resident in HBM before the
-timed region.  Prints ONE JSON line (see README / DESIGN for the fields).
+timed region.  Prints ONE JSON line: throughput of the timed steps, the roofline fraction of
+the round kernels, and the CPU oracle's rate on the host cores for comparison.
 
   python bench.py [--steps K] [--warmup W] [--config 2] [--order fixed|fast]
 """
