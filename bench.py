@@ -65,7 +65,7 @@ class Workload:
     generator (outside any timed region)."""
 
     def __init__(self, k: int, order: str, launch: dict | None = None, stagger: int = 0,
-                 clip: int = 0, stats: bool = False):
+                 clip: int = 0, stats: bool = False, unfused: bool = False):
         import torch
         from paper_1908_04207_amd import binding as eb
         from workloads import grads as wg
@@ -100,6 +100,9 @@ class Workload:
             self.stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
             self.stats_ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
             self.ctx.eager_stats_attach(self.stats, self.stats_ws, nbytes)
+        self.unfused = unfused
+        if unfused:    # A/B: receive buffer first, update rule as a second pass
+            self.recv = torch.empty(n, device=dev)
         self.step_no = 0
         self.q_prev = 0
         # argument marshalling done once: pointer tables, the stream handle
@@ -128,8 +131,14 @@ class Workload:
         """One step; returns its algorithmic bytes."""
         cfg = self.cfg
         plan = self.last_plan = self.plan(self.step_no)
-        self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=None,
-                                         opt=(self.w, self.v, cfg.lr, cfg.mu), stream=self.stream)
+        if self.unfused:
+            self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=self.recv, opt=None,
+                                             stream=self.stream)
+            self.ctx.eager_sgd_step(self.recv, (self.w, self.v, cfg.lr, cfg.mu), stream=self.stream)
+        else:
+            self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=None,
+                                             opt=(self.w, self.v, cfg.lr, cfg.mu),
+                                             stream=self.stream)
         q_now = cfg.P - plan.nap
         b = alg_bytes_per_element(cfg.P, self.gbytes, self.q_prev, q_now) * cfg.numel
         self.q_prev = q_now
@@ -138,13 +147,13 @@ class Workload:
 
 
 def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0, clip=0,
-            stats=False):
+            stats=False, unfused=False):
     """W untimed steps, then K timed steps.  Returns the workload, the wall-clock seconds
     of the K steps (synchronised on both sides), their algorithmic bytes, and the GPU time
     of the same K steps between two HIP events recorded on the launch stream (torch's
     current stream, which is the one the binding launches on)."""
     import torch
-    wl = Workload(k, order, launch, stagger, clip, stats)
+    wl = Workload(k, order, launch, stagger, clip, stats, unfused)
     wl.prepare(0, warmup + steps)
     for _ in range(warmup):
         wl.step()
@@ -279,6 +288,9 @@ def main() -> int:
     ap.add_argument("--trace", default="", metavar="FILE",
                     help="after the timed run, log this many more steps one by one to FILE "
                          "(JSON lines: NAP, initiator, mask, bytes, GPU microseconds)")
+    ap.add_argument("--unfused", action="store_true",
+                    help="A/B: partial allreduce into a receive buffer, then eager_sgd_step (same "
+                         "algorithmic bytes in the numerator, 8 B/element more traffic)")
     ap.add_argument("--stats", action="store_true",
                     help="also compute the per-bucket norms in every round (eager_stats_attach)")
     a = ap.parse_args()
@@ -292,7 +304,7 @@ def main() -> int:
         return 2
     launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
     wl, wall, nbytes, kern_s = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger,
-                                       a.clip, a.stats)
+                                       a.clip, a.stats, a.unfused)
     cfg = wl.cfg
     total_b = sum(nbytes)
     traffic = MEASURED_TRAFFIC.get(cfg.name)
@@ -308,7 +320,7 @@ def main() -> int:
         "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode,
                    "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
                    "order": a.order, "launch": launch, "stagger": a.stagger,
-                   "bucket_stats": a.stats},
+                   "bucket_stats": a.stats, "unfused": a.unfused},
         "steps_per_s": round(a.steps / wall, 2),
         "pct_hbm_peak": round(100.0 * total_b / wall / 1e9 / HBM_PEAK_GBS, 2),
         "alg_bytes_per_step": round(total_b / a.steps),
