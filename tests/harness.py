@@ -18,6 +18,19 @@ from workloads import times as wt
 NT_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
+def paper_values() -> dict:
+    """tests/golden/paper_reported_values.txt as {key: float}."""
+    import os
+    out = {}
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden",
+                        "paper_reported_values.txt")
+    for line in open(path):
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            out[line[0]] = float(line[1])
+    return out
+
+
 def as_oracle_grad(t: torch.Tensor) -> np.ndarray:
     """CPU tensor -> what the oracle takes (float32, or uint16 bit patterns for bf16)."""
     t = t.detach().cpu().contiguous()

@@ -101,8 +101,12 @@ def test_microbenchmark_latency_shape_and_nap():
     (53.32x for solo, 2.46x for majority over the full allreduce) fall where those forms put
     them for a collective of a few hundred microseconds.  NAP: exactly 1 for solo, rank of
     the initiator + 1 for majority, about half the processes on average."""
-    P, iters = 32, 64
-    arrival = [float(p + 1) for p in range(P)]
+    from harness import paper_values
+    pv = paper_values()
+    P, iters = int(pv["microbench_processes"]), int(pv["microbench_iterations"])
+    arrival = [float(p) for p in range(int(pv["microbench_skew_first_ms"]),
+                                       int(pv["microbench_skew_last_ms"]) + 1)]
+    assert len(arrival) == P
 
     def mean_wait(plans):
         return sum(sum(max(0.0, arrival[pl.initiator] - a) for a in arrival) / P
@@ -110,7 +114,7 @@ def test_microbenchmark_latency_shape_and_nap():
 
     solo = [eb.eager_plan_participation(eb.SOLO, arrival, 3, t) for t in range(iters)]
     full = [eb.eager_plan_quorum(arrival, P, t) for t in range(iters)]
-    assert all(pl.nap == 1 and pl.initiator == 0 for pl in solo)
+    assert all(pl.nap == pv["microbench_solo_nap"] and pl.initiator == 0 for pl in solo)
     assert all(pl.nap == P and pl.initiator == P - 1 for pl in full)
     assert mean_wait(solo) == 0.0
     assert mean_wait(full) == (P - 1) / 2.0                       # mean of 31, 30, ..., 0 ms
@@ -122,11 +126,12 @@ def test_microbenchmark_latency_shape_and_nap():
         waits.append(mean_wait(maj))
     # initiator uniform over the ranks: E[NAP] = (P+1)/2, E[wait] = (P^2 - 1) / (6 P) ms
     assert abs(np.mean(naps) - (P + 1) / 2.0) < 0.15
+    assert abs(np.mean(naps) - pv["microbench_majority_nap"]) < 1.0
     assert abs(np.mean(waits) - (P * P - 1) / (6.0 * P)) < 0.1
     t_c = 0.3                                                     # ms, a small-message allreduce
     lat_full, lat_solo, lat_maj = (P - 1) / 2.0 + t_c, t_c, float(np.mean(waits)) + t_c
-    assert 40 < lat_full / lat_solo < 70                          # the paper reports 53.32x
-    assert 2.0 < lat_full / lat_maj < 3.5                         # the paper reports 2.46x
+    assert 0.75 < (lat_full / lat_solo) / pv["microbench_solo_latency_ratio"] < 1.3
+    assert 0.8 < (lat_full / lat_maj) / pv["microbench_majority_latency_ratio"] < 1.4
     assert lat_solo < lat_maj < lat_full
 
 

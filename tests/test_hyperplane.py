@@ -65,8 +65,12 @@ def test_eager_sgd_converges_like_synchronous_sgd(hp):
 
 
 def test_time_model_reproduces_the_reported_speedups():
+    from harness import paper_values
     from paper_1908_04207_amd import hyperplane as hp
-    for delay, reported in ((200.0, 1.50), (300.0, 1.75), (400.0, 2.01)):
+    pv = paper_values()
+    assert pv["hyperplane_processes"] == 8 and pv["hyperplane_parameters"] == 8192 + 1
+    for delay in (200.0, 300.0, 400.0):
+        reported = pv[f"hyperplane_speedup_{int(delay)}ms"]
         t_sync = t_solo = 0.0
         for t in range(2000):
             arr = hp.arrival_times(8, 7, t, 400.0, delay)
