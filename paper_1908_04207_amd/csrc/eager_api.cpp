@@ -67,6 +67,7 @@ int64_t max_records(const eager_ctx *ctx)
     const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
     return span / 256 + 8;
 }
+
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
 // the reduction instead of inside it.
 bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid,
