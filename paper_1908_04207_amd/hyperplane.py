@@ -39,12 +39,15 @@ def _hash(seed: int, step: int, tag: int) -> int:
 
 
 def arrival_times(P: int, seed: int, step: int, base_ms: float, delay_ms: float,
-                  jitter: float = 0.01) -> List[float]:
-    """Arrival of each process at the collective of `step`, ms from the round's origin."""
+                  jitter: float = 0.01, delayed_ranks: int = 1) -> List[float]:
+    """Arrival of each process at the collective of `step`, ms from the round's origin.
+    `delayed_ranks` seeded random ranks (the paper delays 1 of 8, or 4 of 64) get delay_ms on
+    top; draws may coincide, then fewer ranks are delayed."""
     t = [base_ms * (1.0 + jitter * ((_hash(seed, step, 1 + p) >> 11) / 2.0 ** 53 - 0.5))
          for p in range(P)]
     # tag 0 would reproduce the library's draw of the majority initiator for the same seed
-    t[_hash(seed, step, 1000) % P] += delay_ms
+    for d in {_hash(seed, step, 1000 + i) % P for i in range(delayed_ranks)}:
+        t[d] += delay_ms
     return t
 
 
@@ -62,7 +65,7 @@ def train(mode: str = "solo", steps: int = 200, P: int = 8, dim: int = 8192,
           total_batch: int = 2048, delay_ms: float = 300.0, base_ms: float = 400.0,
           lr: float = 0.01, mu: float = 0.9, noise: float = 2.0, seed: int = 20190804,
           quorum: int = 0, eval_every: int = 10, order: int = eb.ORDER_FIXED,
-          on_round: Optional[Callable] = None) -> Result:
+          on_round: Optional[Callable] = None, delayed_ranks: int = 1) -> Result:
     """Train the hyperplane model for `steps` rounds.  mode: "solo", "majority", "quorum"
     (with `quorum` = k) or "sync" (= quorum P, ordinary synchronous SGD).
 
@@ -95,7 +98,7 @@ def train(mode: str = "solo", steps: int = 200, P: int = 8, dim: int = 8192,
             G[p][:dim] = (2.0 / bs) * (X.t() @ err)
             G[p][dim] = 2.0 * err.mean()
         # eager-SGD: who is on time, then one fused round in the library
-        arr = arrival_times(P, seed, t, base_ms, delay_ms)
+        arr = arrival_times(P, seed, t, base_ms, delay_ms, delayed_ranks=delayed_ranks)
         if mode == "solo":
             plan = eb.eager_plan_participation(eb.SOLO, arr, seed, t)
         elif mode == "majority":
@@ -123,7 +126,19 @@ def main() -> None:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--delay-ms", type=float, nargs="*", default=[200.0, 300.0, 400.0])
+    ap.add_argument("--quorum-sweep", action="store_true",
+                    help="the spectrum between solo (k = 1) and synchronous SGD (k = P) that the "
+                         "paper's conclusions propose: k-of-P rounds for every k, 300 ms delay on "
+                         "two random ranks per step")
     a = ap.parse_args()
+    if a.quorum_sweep:
+        P = 8
+        runs = [train("quorum", a.steps, P=P, quorum=k, delay_ms=300.0, delayed_ranks=2)
+                for k in range(1, P + 1)]
+        for k, r in enumerate(runs, 1):
+            print(f"quorum {k} of {P}  NAP {r.nap_mean:4.2f}  simulated {r.sim_ms / 1e3:7.1f} s "
+                  f"({runs[-1].sim_ms / r.sim_ms:.2f}x synchronous)  validation MSE {r.val_loss[-1]:.3f}")
+        return
     for d in a.delay_ms:
         runs = {m: train(m, a.steps, delay_ms=d) for m in ("sync", "majority", "solo")}
         for m, r in runs.items():

@@ -64,6 +64,25 @@ def test_eager_sgd_converges_like_synchronous_sgd(hp):
     assert runs["solo"].sim_ms < runs["majority"].sim_ms < sync.sim_ms
 
 
+@pytest.mark.gpu
+def test_quorum_spectrum_trades_time_for_freshness(hp):
+    """k-of-P rounds (the spectrum between solo and synchronous SGD, Section 9) with two
+    delayed ranks per step: more required arrivals mean more active processes and more
+    simulated time per step, never less; k = P is synchronous SGD; every k converges."""
+    P = 8
+    runs = [hp.train("quorum", 300, P=P, quorum=k, delay_ms=300.0, delayed_ranks=2)
+            for k in (1, 3, 6, 7, 8)]
+    naps = [r.nap_mean for r in runs]
+    times = [r.sim_ms for r in runs]
+    assert naps == sorted(naps) and times == sorted(times)
+    assert naps[0] == 1.0 and naps[-1] == float(P)
+    assert times[2] < 0.8 * times[-1]          # 6 of 8 never waits for both delayed ranks
+    sync = hp.train("sync", 300, P=P, delay_ms=300.0, delayed_ranks=2)
+    assert sync.sim_ms == runs[-1].sim_ms and sync.val_loss == runs[-1].val_loss
+    for r in runs:
+        assert r.val_loss[-1] < 0.05 * r.val_loss[0]
+
+
 def test_time_model_reproduces_the_reported_speedups():
     from harness import paper_values
     from paper_1908_04207_amd import hyperplane as hp
