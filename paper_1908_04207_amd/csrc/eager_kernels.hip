@@ -342,18 +342,6 @@ __global__ __launch_bounds__(LB) void round_kernel(const RoundArgs)
 }
 
 // ---------------------------------------------------------------------------------------
-// Compacted form: a list of streams ("slots"), each with one action, in summation order.  A
-// chunk of C slots is C loads issued back to back, then the adds, then the stores; the list
-// is consumed in chunks of CH and one remainder chunk of its exact size, so that not a
-// single stand-in load is issued.
-//
-// A lane owns 4 consecutive elements of every stream, so that each load or store instruction
-// of a wavefront covers one contiguous kilobyte of an fp32 stream.  With bf16 gradients
-// (BF16) the lane's 4 gradient elements are 8 bytes, one half of an aligned 16-byte piece:
-// lanes 2k and 2k+1 load the same piece and each keeps its half.  That way every load of a
-// chunk is the same 16-byte instruction whatever the type of its stream - the type, like the
-// action, is a scalar select and never a branch around a load.
-// ---------------------------------------------------------------------------------------
 // Per-bucket by-products (optional): sum of squares of the averaged update and of the
 // parameters, count of non-finite elements.  They are reductions ACROSS elements, the one
 // place on this path where cross-lane work belongs: a lane sums its 4 elements, the 64 lanes
@@ -457,6 +445,18 @@ __device__ __forceinline__ void stats_commit(StatsRecord *records, StatsRecord *
     if ((threadIdx.x & 63u) == 0u) records[wave_index] = rec;
 }
 
+// ---------------------------------------------------------------------------------------
+// Compacted form: a list of streams ("slots"), each with one action, in summation order.  A
+// chunk of C slots is C loads issued back to back, then the adds, then the stores; the list
+// is consumed in chunks of CH and one remainder chunk of its exact size, so that not a
+// single stand-in load is issued.
+//
+// A lane owns 4 consecutive elements of every stream, so that each load or store instruction
+// of a wavefront covers one contiguous kilobyte of an fp32 stream.  With bf16 gradients
+// (BF16) the lane's 4 gradient elements are 8 bytes, one half of an aligned 16-byte piece:
+// lanes 2k and 2k+1 load the same piece and each keeps its half.  That way every load of a
+// chunk is the same 16-byte instruction whatever the type of its stream - the type, like the
+// action, is a scalar select and never a branch around a load.
 struct LaneVec {
     long long e;        // first of the lane's 4 elements (arena index)
     long long off_bf;   // byte offset of the 16-byte piece of a bf16 stream that holds them
