@@ -142,7 +142,7 @@ int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step
  *           4.1.1: holds the value of the latest execution)
  *   opt     host or NULL.  Non-NULL: w and v are updated in the same pass.  NULL:
  *           only recv is produced (then recv must not be NULL)
- * On success the validity of every bucket in the range becomes ~mask.
+ * On success the validity of every bucket in the range becomes ~mask (the late processes).
  * The three entry points run the same kernels and differ in what they accept:
  * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY, _quorum EAGER_QUORUM.
  * Errors: EINVAL (NULL, alignment, b0 >= b1, range), ESTATE (mode or P mismatch,
@@ -159,6 +159,28 @@ int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int
 int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                    const void *const *grads, float *const *resid,
                                    float *recv, const eager_opt *opt, void *stream);
+
+/*
+ * Processes that lag by more than one round (Section 5, last paragraph).  The entry points
+ * above assume that every process that is not on time still finishes its gradient before
+ * the next round (it is stored into the send buffer as part of the round).  With
+ * eager_partial_allreduce_lagging, processes in `absent` (a mask disjoint from plan->mask)
+ * finish no gradient in this round's window: they contribute what their send buffer holds
+ * and store nothing (grads[p] is not read and may be NULL); afterwards their send buffer is
+ * empty.  Any plan mode is accepted.  When such a process finishes a gradient later, between
+ * two rounds, eager_stash puts it into the send buffer of buckets [b0, b1): R_p <- G if the
+ * buffer is empty, R_p <- R_p + G if it still holds an undelivered gradient (one fp32 add
+ * per element, buffer first), and marks the buffer non-empty.  A late process of a round is
+ * exactly an absent one followed by eager_stash of its gradient.
+ * Errors: as eager_partial_allreduce_*; ESTATE if absent intersects plan->mask or has bits
+ * beyond P; eager_stash: EINVAL (NULL, alignment, process or range outside), EDEVICE.
+ */
+int eager_partial_allreduce_lagging(eager_ctx *ctx, const eager_plan *plan, uint64_t absent,
+                                    int b0, int b1, const void *const *grads,
+                                    float *const *resid, float *recv, const eager_opt *opt,
+                                    void *stream);
+int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,
+                void *stream);
 
 /* The update rule alone (Algorithm 2, lines 7-8) on buckets [b0, b1): reads u from
  * `update` (device fp32 arena, e.g. a receive buffer), updates opt->params/momentum.

@@ -74,6 +74,10 @@ static inline void update_rule(float u, float *w, float *v, float lr, float mu, 
  *   mask         bit p set: process p is active in this round (s_t^p = true)
  *   w, v         parameters and momentum (fp32, n elements), updated in place; both may
  *                be NULL to skip the update rule
+ *   absent       bit p set (only where mask's bit is clear): process p has not finished a
+ *                gradient in this round's window either (it lags by more than one round,
+ *                last paragraph of Section 5): it contributes what its send buffer holds
+ *                and stores nothing; G[p] is not read
  *   wd, nesterov variants of the update rule (0, 0 = heavy-ball momentum SGD)
  *   recv         receive buffer, gets the averaged result u; may be NULL
  *   nthreads     1 = the scalar reference; >1 = same loop body, elements partitioned
@@ -82,11 +86,11 @@ static inline void update_rule(float u, float *w, float *v, float lr, float mu, 
  * After the call the caller sets valid' = ~mask (on-time processes emptied their send
  * buffer, late ones stored the gradient they finished late).
  */
-void eager_oracle_round_ex(int P, int64_t n,
-                           const void *const *G, int grad_is_bf16,
-                           float *const *R, uint64_t valid, uint64_t mask,
-                           float *w, float *v, float lr, float mu, float wd, int nesterov,
-                           float *recv, int nthreads)
+void eager_oracle_round_async(int P, int64_t n,
+                              const void *const *G, int grad_is_bf16,
+                              float *const *R, uint64_t valid, uint64_t mask, uint64_t absent,
+                              float *w, float *v, float lr, float mu, float wd, int nesterov,
+                              float *recv, int nthreads)
 {
     const float inv_P = 1.0f / (float)P;
     int64_t i;
@@ -96,10 +100,13 @@ void eager_oracle_round_ex(int P, int64_t n,
         float s = 0.0f;
         int p;
         for (p = 0; p < P; ++p) {
-            const float g = grad_is_bf16 ? widen_bf16(((const uint16_t *)G[p])[i])
-                                         : ((const float *)G[p])[i];
             const int on_time = (int)((mask >> p) & 1u);
             const int has_stale = (int)((valid >> p) & 1u);
+            const int is_absent = (int)((absent >> p) & 1u);
+            float g = 0.0f;
+            if (!is_absent)
+                g = grad_is_bf16 ? widen_bf16(((const uint16_t *)G[p])[i])
+                                 : ((const float *)G[p])[i];
             if (on_time) {
                 /* contributes stale + fresh; its send buffer becomes G_null */
                 float c = g;
@@ -107,10 +114,12 @@ void eager_oracle_round_ex(int P, int64_t n,
                     c = R[p][i] + g;
                 s = s + c;
             } else {
-                /* contributes only what was pending; the late gradient is stored */
+                /* contributes only what was pending; the late gradient is stored (a process
+                 * that is still computing has none to store) */
                 if (has_stale)
                     s = s + R[p][i];
-                R[p][i] = g;
+                if (!is_absent)
+                    R[p][i] = g;
             }
         }
         {
@@ -120,6 +129,29 @@ void eager_oracle_round_ex(int P, int64_t n,
             if (recv)
                 recv[i] = u;
         }
+    }
+}
+
+void eager_oracle_round_ex(int P, int64_t n,
+                           const void *const *G, int grad_is_bf16,
+                           float *const *R, uint64_t valid, uint64_t mask,
+                           float *w, float *v, float lr, float mu, float wd, int nesterov,
+                           float *recv, int nthreads)
+{
+    eager_oracle_round_async(P, n, G, grad_is_bf16, R, valid, mask, 0u, w, v, lr, mu, wd,
+                             nesterov, recv, nthreads);
+}
+
+/* A process that finishes a gradient after the round it was computed for has been executed
+ * puts it into its send buffer (Section 5): the buffer holds it alone if it was empty,
+ * else the sum of what it held and the new gradient (a process that lags by several
+ * rounds may finish two gradients between two executions). */
+void eager_oracle_stash(int64_t n, const void *G, int grad_is_bf16, float *R, int has_stale)
+{
+    int64_t i;
+    for (i = 0; i < n; ++i) {
+        const float g = grad_is_bf16 ? widen_bf16(((const uint16_t *)G)[i]) : ((const float *)G)[i];
+        R[i] = has_stale ? R[i] + g : g;
     }
 }
 

@@ -55,6 +55,15 @@ def _load():
             ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64, ctypes.c_uint64,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
             ctypes.c_void_p, ctypes.c_int]
+        lib.eager_oracle_round_async.restype = None
+        lib.eager_oracle_round_async.argtypes = [
+            ctypes.c_int, ctypes.c_int64, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+            ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_float, ctypes.c_float,
+            ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_int]
+        lib.eager_oracle_stash.restype = None
+        lib.eager_oracle_stash.argtypes = [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int,
+                                           ctypes.c_void_p, ctypes.c_int]
         lib.eager_oracle_round_ex.restype = None
         lib.eager_oracle_round_ex.argtypes = [
             ctypes.c_int, ctypes.c_int64, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
@@ -152,13 +161,17 @@ def _ptr_array(arrs: Sequence[np.ndarray]):
 def round_f32(G: Sequence[np.ndarray], R: Sequence[np.ndarray], valid: int, mask: int,
               w: Optional[np.ndarray], v: Optional[np.ndarray], lr: float, mu: float,
               recv: Optional[np.ndarray] = None, nthreads: int = 1,
-              wd: float = 0.0, nesterov: bool = False) -> int:
+              wd: float = 0.0, nesterov: bool = False, absent: int = 0) -> int:
     """One round on one bucket, in place.  G[p]: float32 or uint16 (bf16 bit patterns);
     R[p], w, v, recv: float32.  wd, nesterov: variants of the update rule (off by
-    default).  Returns the new validity mask (~mask over P bits)."""
+    default).  absent: processes (not in mask) that finish no gradient in this round's
+    window: they contribute their send buffer and store nothing; their G[p] is not read
+    (pass any array of the right shape).  Returns the new validity mask (the late
+    processes that stored a gradient)."""
     P = len(G)
     n = G[0].shape[0]
     bf16 = G[0].dtype == np.uint16
+    assert absent & mask == 0
     for p in range(P):
         assert G[p].dtype == (np.uint16 if bf16 else np.float32) and G[p].shape == (n,)
         assert R[p].dtype == np.float32 and R[p].shape == (n,)
@@ -166,11 +179,21 @@ def round_f32(G: Sequence[np.ndarray], R: Sequence[np.ndarray], valid: int, mask
     for x in (w, v, recv):
         assert x is None or (x.dtype == np.float32 and x.shape == (n,) and x.flags.c_contiguous)
     assert (w is None) == (v is None)
-    _load().eager_oracle_round_ex(
-        P, n, _ptr_array(G), int(bf16), _ptr_array(R), valid & _M64, mask & _M64,
+    _load().eager_oracle_round_async(
+        P, n, _ptr_array(G), int(bf16), _ptr_array(R), valid & _M64, mask & _M64, absent & _M64,
         None if w is None else w.ctypes.data, None if v is None else v.ctypes.data,
         lr, mu, wd, int(nesterov), None if recv is None else recv.ctypes.data, nthreads)
-    return ~mask & ((1 << P) - 1)
+    return ~mask & ~absent & ((1 << P) - 1)
+
+
+def stash_f32(G: np.ndarray, R: np.ndarray, has_stale: bool) -> None:
+    """A gradient finished too late for its round goes into the send buffer: R = G if the
+    buffer was empty, else R = R + G."""
+    bf16 = G.dtype == np.uint16
+    assert G.dtype == (np.uint16 if bf16 else np.float32) and R.dtype == np.float32
+    assert G.shape == R.shape and G.flags.c_contiguous and R.flags.c_contiguous
+    _load().eager_oracle_stash(G.shape[0], G.ctypes.data, int(bf16), R.ctypes.data,
+                               int(has_stale))
 
 
 def sgd_f32(u: np.ndarray, w: np.ndarray, v: np.ndarray, lr: float, mu: float,
@@ -231,7 +254,7 @@ class OracleState:
 
     def round(self, mask: int, G: Sequence[np.ndarray], b0: int = 0,
               b1: Optional[int] = None, recv: Optional[np.ndarray] = None,
-              fused: bool = True, nthreads: int = 1) -> None:
+              fused: bool = True, nthreads: int = 1, absent: int = 0) -> None:
         b1 = len(self.numel) if b1 is None else b1
         for b in range(b0, b1):
             lo, hi = self.offset[b], self.offset[b] + self.numel[b]
@@ -239,7 +262,14 @@ class OracleState:
                 [g[lo:hi] for g in G], [r[lo:hi] for r in self.R], self.valid[b], mask,
                 self.w[lo:hi] if fused else None, self.v[lo:hi] if fused else None,
                 self.lr, self.mu, None if recv is None else recv[lo:hi], nthreads,
-                self.wd, self.nesterov)
+                self.wd, self.nesterov, absent)
+
+    def stash(self, p: int, G: np.ndarray, b0: int = 0, b1: Optional[int] = None) -> None:
+        b1 = len(self.numel) if b1 is None else b1
+        for b in range(b0, b1):
+            lo, hi = self.offset[b], self.offset[b] + self.numel[b]
+            stash_f32(G[lo:hi], self.R[p][lo:hi], bool((self.valid[b] >> p) & 1))
+            self.valid[b] |= 1 << p
 
     def sgd(self, u: np.ndarray, b0: int = 0, b1: Optional[int] = None,
             nthreads: int = 1) -> None:

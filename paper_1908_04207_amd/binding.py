@@ -25,7 +25,7 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_sgd_step", "eager_set_update_rule", "eager_stats_workspace_bytes",
+    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
 )
@@ -80,6 +80,10 @@ def _load() -> ctypes.CDLL:
               lib.eager_partial_allreduce_quorum):
         f.argtypes = [vp, ctypes.POINTER(Plan), i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp),
                       vp, ctypes.POINTER(Opt), vp]
+    lib.eager_partial_allreduce_lagging.argtypes = [
+        vp, ctypes.POINTER(Plan), u64, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+        ctypes.POINTER(Opt), vp]
+    lib.eager_stash.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
     lib.eager_get_valid.argtypes = [vp, i32, ctypes.POINTER(u64)]
     lib.eager_set_valid.argtypes = [vp, i32, u64]
@@ -209,6 +213,20 @@ class Context:
                                        b0: int = 0, b1: Optional[int] = None, stream=None):
         self._allreduce(lib.eager_partial_allreduce_quorum, "eager_partial_allreduce_quorum",
                         plan, grads, resid, recv, opt, b0, b1, stream)
+
+    def eager_partial_allreduce_lagging(self, plan: Plan, absent: int, grads, resid, recv=None,
+                                        opt=None, b0: int = 0, b1: Optional[int] = None,
+                                        stream=None):
+        """grads[p] may be None for the processes in `absent`."""
+        fn = lambda h, pl, *rest: lib.eager_partial_allreduce_lagging(h, pl, absent, *rest)  # noqa: E731
+        self._allreduce(fn, "eager_partial_allreduce_lagging", plan, grads, resid, recv, opt, b0,
+                        b1, stream)
+
+    def eager_stash(self, process: int, grad, resid, b0: int = 0, b1: Optional[int] = None,
+                    stream=None) -> None:
+        b1 = self.n_buckets if b1 is None else b1
+        self._check(lib.eager_stash(self._h, process, b0, b1, _ptr(grad), _ptr(resid),
+                                    _stream(stream)), "eager_stash")
 
     def eager_partial_allreduce(self, plan: Plan, *a, **kw):
         """Dispatch on plan.mode to the entry point of that name."""

@@ -108,9 +108,10 @@ int check_opt(eager_ctx *ctx, const eager_opt *opt)
     return EAGER_OK;
 }
 
-int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int b0, int b1,
-                      const void *const *grads, float *const *resid, float *recv,
-                      const eager_opt *opt, void *stream)
+// want_mode < 0: any mode.  absent: processes outside the mask that store no gradient.
+int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uint64_t absent,
+                      int b0, int b1, const void *const *grads, float *const *resid,
+                      float *recv, const eager_opt *opt, void *stream)
 {
     if (!ctx) return EAGER_EINVAL;
     if (!plan || !grads || !resid) return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
@@ -122,9 +123,13 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
     }
     if (recv && !aligned16(recv)) return fail(ctx, EAGER_EINVAL, "recv must be 16-byte aligned");
     const int P = ctx->P;
-    if (plan->mode != want_mode)
+    if (want_mode >= 0 && plan->mode != want_mode)
         return fail(ctx, EAGER_ESTATE, "plan->mode %d does not match this entry point (%d)",
                     plan->mode, want_mode);
+    if (plan->mode < EAGER_SOLO || plan->mode > EAGER_QUORUM)
+        return fail(ctx, EAGER_ESTATE, "plan->mode %d is not a mode", plan->mode);
+    if (absent & plan->mask) return fail(ctx, EAGER_ESTATE, "an absent process cannot be active");
+    if (absent & ~low_bits(P)) return fail(ctx, EAGER_ESTATE, "absent mask has bits beyond P");
     if (plan->P != P) return fail(ctx, EAGER_ESTATE, "plan->P %d != context P %d", plan->P, P);
     if (plan->mask & ~low_bits(P)) return fail(ctx, EAGER_ESTATE, "plan->mask has bits beyond P");
     if (plan->nap != popcount64(plan->mask) || plan->nap < 1)
@@ -132,8 +137,10 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
     if (plan->initiator < 0 || plan->initiator >= P || !((plan->mask >> plan->initiator) & 1ull))
         return fail(ctx, EAGER_ESTATE, "initiator %d is not in the mask", plan->initiator);
     for (int p = 0; p < P; ++p) {
-        if (!grads[p] || !resid[p]) return fail(ctx, EAGER_EINVAL, "grads[%d] or resid[%d] is NULL", p, p);
-        if (!aligned16(grads[p]) || !aligned16(resid[p]))
+        const bool needs_g = !((absent >> p) & 1ull);       // an absent process has no gradient
+        if ((needs_g && !grads[p]) || !resid[p])
+            return fail(ctx, EAGER_EINVAL, "grads[%d] or resid[%d] is NULL", p, p);
+        if ((needs_g && !aligned16(grads[p])) || !aligned16(resid[p]))
             return fail(ctx, EAGER_EINVAL, "grads[%d] / resid[%d] must be 16-byte aligned", p, p);
     }
     for (int b = b0; b < b1; ++b)
@@ -180,10 +187,12 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
         a.valid = ctx->valid[b];
         a.e0 = ctx->offset[b];
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
-        a.dummy = static_cast<const char *>(grads[0]) + a.e0 * (ctx->bf16 ? 2 : 4);
-        const uint64_t late = ~plan->mask & low_bits(P);
-        const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask, a.valid, a.n);
-        a.gload = split ? plan->mask : low_bits(P);
+        // stand-in address of the rank-chunk kernel: 16 readable bytes (the initiator is
+        // never absent, so its gradient exists)
+        a.dummy = static_cast<const char *>(grads[plan->initiator]) + a.e0 * (ctx->bf16 ? 2 : 4);
+        const uint64_t late = ~plan->mask & ~absent & low_bits(P);   // finish a gradient late
+        const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
+        a.gload = split ? plan->mask : (plan->mask | late);
         a.store = split ? 0 : late;
         if (ctx->stats) {
             a.stats.e0 = a.e0;
@@ -220,7 +229,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, int
                             hipGetErrorString(he));
         }
         for (int k = b; k < e; ++k) {
-            ctx->valid[k] = ~plan->mask & low_bits(P);
+            ctx->valid[k] = late;
             ctx->last_step[k] = plan->step;
             ctx->stepped[k] = 1;
         }
@@ -368,21 +377,59 @@ int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0,
                                  const void *const *grads, float *const *resid, float *recv,
                                  const eager_opt *opt, void *stream)
 {
-    return partial_allreduce(ctx, EAGER_SOLO, plan, b0, b1, grads, resid, recv, opt, stream);
+    return partial_allreduce(ctx, EAGER_SOLO, plan, 0, b0, b1, grads, resid, recv, opt, stream);
 }
 
 int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                      const void *const *grads, float *const *resid, float *recv,
                                      const eager_opt *opt, void *stream)
 {
-    return partial_allreduce(ctx, EAGER_MAJORITY, plan, b0, b1, grads, resid, recv, opt, stream);
+    return partial_allreduce(ctx, EAGER_MAJORITY, plan, 0, b0, b1, grads, resid, recv, opt, stream);
 }
 
 int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                    const void *const *grads, float *const *resid, float *recv,
                                    const eager_opt *opt, void *stream)
 {
-    return partial_allreduce(ctx, EAGER_QUORUM, plan, b0, b1, grads, resid, recv, opt, stream);
+    return partial_allreduce(ctx, EAGER_QUORUM, plan, 0, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_partial_allreduce_lagging(eager_ctx *ctx, const eager_plan *plan, uint64_t absent,
+                                    int b0, int b1, const void *const *grads,
+                                    float *const *resid, float *recv, const eager_opt *opt,
+                                    void *stream)
+{
+    return partial_allreduce(ctx, -1, plan, absent, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,
+                void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (process < 0 || process >= ctx->P) return fail(ctx, EAGER_EINVAL, "process %d out of range", process);
+    if (!grad || !resid) return fail(ctx, EAGER_EINVAL, "grad and resid must not be NULL");
+    if (!aligned16(grad) || !aligned16(resid))
+        return fail(ctx, EAGER_EINVAL, "grad and resid must be 16-byte aligned");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    const uint64_t bit = 1ull << process;
+    int b = b0;
+    while (b < b1) {                     // runs of buckets whose send buffer is in the same state
+        int e = b + 1;
+        while (e < b1 && ((ctx->valid[e] ^ ctx->valid[b]) & bit) == 0) ++e;
+        eager::StashArgs a;
+        a.g = grad;
+        a.r = resid;
+        a.e0 = ctx->offset[b];
+        a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
+        a.accumulate = (ctx->valid[b] & bit) ? 1 : 0;
+        hipError_t he = eager::launch_stash(a, ctx->bf16, static_cast<hipStream_t>(stream));
+        if (he != hipSuccess)
+            return fail(ctx, EAGER_EDEVICE, "stash kernel launch failed: %s", hipGetErrorString(he));
+        for (int k = b; k < e; ++k) ctx->valid[k] |= bit;
+        b = e;
+    }
+    ctx->err.clear();
+    return EAGER_OK;
 }
 
 int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,

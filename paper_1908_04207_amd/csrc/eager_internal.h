@@ -109,6 +109,14 @@ struct CarryArgs {
     long long n;                 // elements in the run
 };
 
+// A gradient finished after its round: R <- G (empty send buffer) or R <- R + G.
+struct StashArgs {
+    const void *g;               // gradient arena base of the process
+    float *r;                    // its send-buffer arena base
+    long long e0, n;             // run
+    int accumulate;              // 1: the send buffer holds an undelivered gradient
+};
+
 struct SgdArgs {
     const float *u;
     float *w;
@@ -145,6 +153,7 @@ hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStr
 hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
 long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch
 int slot_tail(long long n, bool bf16);                       // elements of its ragged tail
+hipError_t launch_stash(const StashArgs &a, bool bf16, hipStream_t stream);
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

@@ -846,6 +846,39 @@ __global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a, unsigned 
     }
 }
 
+// A late gradient outside a round (a process that lags by more than one round, last
+// paragraph of Section 5): R <- G, or R <- R + G if the send buffer still holds an
+// undelivered gradient.  A plain stream, a lane owns 4 elements.
+template <bool BF16>
+__global__ __launch_bounds__(64) void stash_kernel(const StashArgs a)
+{
+    const long long nvec = a.n / 4;
+    const char *src = static_cast<const char *>(a.g);
+    const long long stride = static_cast<long long>(gridDim.x) * blockDim.x;
+    for (long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x; vi < nvec;
+         vi += stride) {
+        const long long e = a.e0 + vi * 4;
+        f32x4 x;
+        if (BF16) {
+            const u32x2 g = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src + e * 2));
+            x.x = __uint_as_float(g.x << 16);
+            x.y = __uint_as_float(g.x & 0xffff0000u);
+            x.z = __uint_as_float(g.y << 16);
+            x.w = __uint_as_float(g.y & 0xffff0000u);
+        } else {
+            x = ld_f4<true>(reinterpret_cast<const float *>(src + e * 4));
+        }
+        if (a.accumulate) x = ld_f4<true>(a.r + e) + x;
+        st_f4<true>(a.r + e, x);
+    }
+    const long long rem = a.n - nvec * 4;
+    if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem) {
+        const long long i = a.e0 + nvec * 4 + threadIdx.x;
+        const float g = load_grad_scalar<BF16>(src, i);
+        a.r[i] = a.accumulate ? a.r[i] + g : g;
+    }
+}
+
 template <bool FAST>
 __global__ __launch_bounds__(256) void sgd_kernel(const SgdArgs a)
 {
@@ -1185,6 +1218,17 @@ hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream)
     const int n = a.b_hi - a.b_lo;
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(stats_finish_kernel, dim3(n), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_stash(const StashArgs &a, bool bf16, hipStream_t stream)
+{
+    if (a.n <= 0) return hipSuccess;
+    long long g = (a.n / 4 + 63) / 64;
+    if (g < 1) g = 1;
+    if (g > kMaxGridThreads / 64) g = kMaxGridThreads / 64;   // the kernel strides
+    if (bf16) hipLaunchKernelGGL(stash_kernel<true>, dim3(static_cast<unsigned>(g)), dim3(64), 0, stream, a);
+    else hipLaunchKernelGGL(stash_kernel<false>, dim3(static_cast<unsigned>(g)), dim3(64), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -22,6 +22,9 @@ int (*const p_majority)(eager_ctx *, const eager_plan *, int, int, const void *c
                         float *, const eager_opt *, void *) = eager_partial_allreduce_majority;
 int (*const p_quorum)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
                       float *, const eager_opt *, void *) = eager_partial_allreduce_quorum;
+int (*const p_lagging)(eager_ctx *, const eager_plan *, uint64_t, int, int, const void *const *,
+                       float *const *, float *, const eager_opt *, void *) = eager_partial_allreduce_lagging;
+int (*const p_stash)(eager_ctx *, int, int, int, const void *, float *, void *) = eager_stash;
 int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
 int (*const p_rule)(eager_ctx *, float, int) = eager_set_update_rule;
 int (*const p_stats_bytes)(const eager_ctx *, int64_t *) = eager_stats_workspace_bytes;

@@ -99,12 +99,24 @@ class Pair:
 
     # -- one round on both sides ---------------------------------------------------------
     def round(self, plan, G_host: List[np.ndarray], b0: int = 0, b1: Optional[int] = None,
-              fused: bool = True, want_recv: bool = False) -> None:
+              fused: bool = True, want_recv: bool = False, absent: Optional[int] = None) -> None:
         opt = (self.w, self.v, self.lr, self.mu) if fused else None
         recv = self.recv if (want_recv or not fused) else None
-        self.ctx.eager_partial_allreduce(plan, self.G, self.R, recv=recv, opt=opt, b0=b0, b1=b1)
+        if absent is None:
+            self.ctx.eager_partial_allreduce(plan, self.G, self.R, recv=recv, opt=opt, b0=b0, b1=b1)
+        else:       # processes that lag by more than a round: no gradient handed over for them
+            G = [None if (absent >> p) & 1 else g for p, g in enumerate(self.G)]
+            self.ctx.eager_partial_allreduce_lagging(plan, absent, G, self.R, recv=recv, opt=opt,
+                                                     b0=b0, b1=b1)
         self.oracle.round(plan.mask, G_host, b0, b1,
-                          recv=self.oracle_recv if recv is not None else None, fused=fused)
+                          recv=self.oracle_recv if recv is not None else None, fused=fused,
+                          absent=absent or 0)
+
+    def stash(self, p: int, g: torch.Tensor, b0: int = 0, b1: Optional[int] = None) -> None:
+        """A gradient of process p finished between two rounds (tensor on the host)."""
+        dev = g.to(self.G[p].device)
+        self.ctx.eager_stash(p, dev, self.R[p], b0, b1)
+        self.oracle.stash(p, as_oracle_grad(g), b0, b1)
 
     def sgd(self, b0: int = 0, b1: Optional[int] = None) -> None:
         self.ctx.eager_sgd_step(self.recv, (self.w, self.v, self.lr, self.mu), b0, b1)

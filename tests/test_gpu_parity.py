@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from harness import Pair, as_oracle_grad, plan_for
+from workloads import grads as wg
 from workloads import shapes
 
 pytestmark = pytest.mark.gpu
@@ -308,6 +309,58 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
         if ref is None:
             ref = pair.w.clone()
         assert torch.equal(ref, pair.w)
+
+
+@pytest.mark.parametrize("dtype,launch", [("f32", {}), ("f32", {"split": 1}), ("f32", {"split": 2}),
+                                          ("f32", {"compact": 0}), ("bf16", {}),
+                                          ("bf16", {"compact": 0, "split": 2})])
+def test_lagging_processes_and_stashed_gradients(eb, dtype, launch):
+    """Processes that lag by more than one round (Section 5, last paragraph): in a round they
+    are neither on time nor late - they store nothing - and the gradients they finish between
+    rounds are stashed, accumulating in the send buffer.  Every combination of on time /
+    late / absent, stashes into empty and non-empty buffers, on bucket ranges that end up in
+    different states; bitwise against the oracle.  Absent processes hand over no gradient
+    pointer."""
+    cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 3), 6001)
+    bt = cfg.buckets
+    P, nb = cfg.P, bt.n_buckets
+    pair = Pair(eb, P, bt.offset, bt.numel, bt.arena_numel, dtype, eb.ORDER_FIXED, seed=29)
+    for key, val in launch.items():
+        pair.ctx.eager_set_launch(key, val)
+    rng = np.random.default_rng(29)
+    full = (1 << P) - 1
+
+    def fresh(step, p):
+        return wg.fill(torch.empty(bt.arena_numel, dtype=pair.dtype), 29, step, p, 1e-3)
+
+    for t in range(7):
+        state = rng.integers(0, 3, P)                       # 0 on time, 1 late, 2 absent
+        state[int(rng.integers(0, P))] = 0
+        if t == 6:
+            state[:] = 0                                    # everybody on time: delivers the rest
+        mask = sum(1 << p for p in range(P) if state[p] == 0)
+        absent = sum(1 << p for p in range(P) if state[p] == 2)
+        plan = eb.make_plan(eb.SOLO if t % 2 else eb.QUORUM, P, t, mask)
+        pair.round(plan, pair.fresh_grads(t), want_recv=True, absent=absent)
+        pair.compare(exact=True, check_recv=True, what=f"lagging t={t} mask={mask:#x} absent={absent:#x}")
+        assert pair.ctx.eager_get_valid(0) == full & ~mask & ~absent
+        if t == 6:
+            break
+        for p in range(P):                                  # gradients finished between rounds
+            if state[p] == 2 or (state[p] == 1 and p % 3 == 0):
+                pair.stash(p, fresh(100 + t, p))            # empty buffer, or on top of the late one
+                if p % 2:
+                    pair.stash(p, fresh(200 + t, p), 0, max(1, nb // 2))   # some buckets only
+        pair.compare(exact=True, what=f"after stashes t={t}")
+    assert all(pair.ctx.eager_get_valid(b) == 0 for b in range(nb))
+    # refused before anything is launched
+    with pytest.raises(eb.EagerError) as e:
+        pair.ctx.eager_partial_allreduce_lagging(eb.make_plan(eb.SOLO, P, 50, 0b11), 0b10, pair.G,
+                                                 pair.R, opt=(pair.w, pair.v, 0.1, 0.9))
+    assert e.value.status == eb.ESTATE                      # absent and active at once
+    with pytest.raises(eb.EagerError) as e:
+        pair.ctx.eager_stash(P, pair.G[0], pair.R[0])
+    assert e.value.status == eb.EINVAL
 
 
 def test_bucket_ranges_on_concurrent_streams(eb):

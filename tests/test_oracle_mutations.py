@@ -38,6 +38,14 @@ MUTATIONS = {
         ("step = fmaf(mu, vn, g);", "step = fmaf(mu, *v, g);"),
     "weight decay applied to the update instead of the parameter":
         ("g = fmaf(wd, *w, u);", "g = fmaf(wd, u, *w);"),
+    "stashed gradient overwrites a pending one":
+        ("R[i] = has_stale ? R[i] + g : g;", "R[i] = g;"),
+    "absent process contributes nothing":
+        ("""                if (has_stale)
+                    s = s + R[p][i];
+                if (!is_absent)""", """                if (has_stale && !is_absent)
+                    s = s + R[p][i];
+                if (!is_absent)"""),
 }
 
 
@@ -54,6 +62,7 @@ def _pins():
     yield pins.test_divides_by_P_not_by_contributors
     yield pins.test_bf16_widening_matches_torch
     yield pins.test_nonfinite_gradients_propagate
+    yield lambda: pins.test_brute_force_with_absent_processes_and_stashes(2, 3)
 
 
 @pytest.mark.parametrize("name", list(MUTATIONS))

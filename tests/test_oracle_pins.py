@@ -206,6 +206,93 @@ def test_lemma2_distance_to_clean_iterate():
         assert float(np.dot(diff, diff)) <= lr ** 2 * late ** 2 * M2 / P ** 2 + 1e-12
 
 
+# ------------------------------------------------------------------ lag of more than one round
+def test_late_is_absent_plus_stash():
+    """A process that is late in a round is one that stores nothing during the round and
+    puts its gradient into the (now empty) send buffer afterwards: the two descriptions of
+    Section 5 give the same bits.  Links the new operations to the pinned round."""
+    rng = np.random.default_rng(11)
+    for P, bf16 in ((2, False), (5, False), (8, True)):
+        n = 37
+        G = [rng.standard_normal(n).astype(np.float32) for _ in range(P)]
+        if bf16:
+            G = [(g.view(np.uint32) >> 16).astype(np.uint16) for g in G]
+        for trial in range(20):
+            mask = int(rng.integers(1, 1 << P))
+            valid = int(rng.integers(0, 1 << P))
+            late = ~mask & ((1 << P) - 1)
+            R0 = [rng.standard_normal(n).astype(np.float32) for _ in range(P)]
+            w0, v0 = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+            Ra, wa, va = [r.copy() for r in R0], w0.copy(), v0.copy()
+            Rb, wb, vb = [r.copy() for r in R0], w0.copy(), v0.copy()
+            val_a = eo.round_f32(G, Ra, valid, mask, wa, va, 0.1, 0.9)
+            val_b = eo.round_f32(G, Rb, valid, mask, wb, vb, 0.1, 0.9, absent=late)
+            assert val_b == 0 and val_a == late
+            for p in range(P):
+                if (late >> p) & 1:
+                    eo.stash_f32(G[p], Rb[p], False)
+                    assert np.array_equal(Ra[p].view(np.uint32), Rb[p].view(np.uint32))
+            assert np.array_equal(wa.view(np.uint32), wb.view(np.uint32))
+            assert np.array_equal(va.view(np.uint32), vb.view(np.uint32))
+
+
+@pytest.mark.parametrize("P,T", [(2, 3), (4, 2), (3, 2)])
+def test_brute_force_with_absent_processes_and_stashes(P, T):
+    """Every sequence of per-process states (on time / late / absent) over T rounds, with
+    extra gradients stashed between rounds (a send buffer then holds a sum): the delivered
+    averages must be exactly what a ledger of delivery times says - a gradient contributed
+    on time is delivered in its round, one finished late or stashed afterwards in the next
+    round - and after a final round with everybody on time every send buffer is empty and
+    every produced gradient has been delivered exactly once (Section 6.1)."""
+    import itertools
+    from fractions import Fraction
+    n = 3
+    states = list(itertools.product((0, 1, 2), repeat=P))          # 0 on time, 1 late, 2 absent
+    states = [s for s in states if 0 in s]                          # somebody triggers the round
+    exact = P in (1, 2, 4)
+
+    def grad(t, p, k):                                              # small integers: exact in fp32
+        return np.array([((t * 5 + p * 3 + k * 7 + i) % 7) - 3 for i in range(n)], dtype=np.float32)
+
+    for seq in itertools.product(states, repeat=T):
+        R, valid = _empty_R(P, n), 0
+        pending = [np.zeros(n) for _ in range(P)]                   # ledger of the send buffers
+        produced = np.zeros(n)
+        delivered = np.zeros(n)
+        for t in range(T + 1):
+            st = seq[t] if t < T else (0,) * P                      # last round: everybody on time
+            mask = sum(1 << p for p in range(P) if st[p] == 0)
+            absent = sum(1 << p for p in range(P) if st[p] == 2)
+            G = [grad(t, p, 0) if t < T else np.zeros(n, dtype=np.float32) for p in range(P)]
+            recv = np.empty(n, dtype=np.float32)
+            valid = eo.round_f32(G, R, valid, mask, None, None, 0, 0, recv, absent=absent)
+            want = np.zeros(n)
+            for p in range(P):
+                want += pending[p]
+                pending[p] = np.zeros(n)
+                if st[p] == 0:
+                    want += G[p]
+                    produced += G[p]
+                elif st[p] == 1:
+                    pending[p] = G[p].astype(np.float64)
+                    produced += G[p]
+            if exact:
+                assert np.array_equal(recv.astype(np.float64) * P, want), (seq, t)
+            else:
+                assert np.allclose(recv.astype(np.float64) * P, want, rtol=0, atol=1e-5), (seq, t)
+            delivered += want
+            if t < T:                                               # extra gradients between rounds
+                for p in range(P):
+                    for k in range(1, 1 + (t + p) % 3 if st[p] != 0 else 1):
+                        g = grad(t, p, k)
+                        eo.stash_f32(g, R[p], bool((valid >> p) & 1))
+                        valid |= 1 << p
+                        pending[p] = pending[p] + g
+                        produced += g
+        assert valid == 0
+        assert np.array_equal(delivered, produced)
+
+
 # ------------------------------------------------------------------ update rule
 def test_momentum_closed_form_and_plain_sgd():
     """Constant averaged gradient g: v_t = g (1 - mu^t) / (1 - mu) and w_t = w_0 - lr *
