@@ -1,0 +1,160 @@
+"""Eager-SGD with a clock, a call counter and a weight view per process (Section 5, last
+paragraph): processes that lag by more than one round, stale gradients that accumulate in the
+send buffer, results missed in the receive buffer, diverging weights, periodic model
+synchronisation.
+
+The CPU tests pin the oracle's event loop against what the paper and arithmetic fix; the GPU
+tests run the library-driven loop (all arithmetic in the kernels) and the oracle's,
+independently, on the same seeded compute times and gradients and compare every state bit
+for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from harness import as_oracle_grad, bits
+from oracle import async_oracle as ao
+from oracle import eager_oracle as eo
+from workloads import grads as wg
+from workloads import times as wt
+
+
+# ------------------------------------------------------------------ CPU: the oracle's loop
+def _int_gradient(n):
+    def g(p, k, w):
+        return np.array([((p * 3 + k * 5 + i) % 7) - 3 for i in range(n)], dtype=np.float32)
+    return g
+
+
+def test_equal_compute_times_are_synchronous_sgd():
+    """Everybody always arrives together: every round is a full allreduce, nobody is ever
+    late, all weight views stay identical and equal ordinary synchronous momentum SGD."""
+    P, n, T = 4, 9, 12
+    rng = np.random.default_rng(0)
+    w0 = rng.standard_normal(n).astype(np.float32)
+    grads = {}
+
+    def g(p, k, w):
+        return grads.setdefault((p, k), rng.standard_normal(n).astype(np.float32))
+    out = ao.simulate(P, n, w0, 0.05, 0.9, "solo", T, lambda p, k: 2.0, g)
+    assert out["nap"] == [P] * T and out["late_calls"] == [0] * P and out["missed"] == [0] * P
+    ref = eo.OracleState(P, [0], [n], n, w0, 0.05, 0.9)
+    for t in range(T):
+        ref.round((1 << P) - 1, [grads[(p, t)] for p in range(P)])
+    for p in range(P):
+        assert np.array_equal(bits(out["w"][p]), bits(ref.w))
+        assert np.array_equal(bits(out["v"][p]), bits(ref.v))
+    assert out["time_ms"] == 2.0 * T
+
+
+@pytest.mark.parametrize("mode,kw", [("solo", {}), ("majority", {"seed": 5}), ("quorum", {"quorum": 2})])
+def test_every_gradient_is_delivered_exactly_once(mode, kw):
+    """Conservation under arbitrary lag (Section 6.1: a rejected update is added later,
+    once): P * sum of all results + what is still in send buffers + the gradients of the
+    processes waiting at the open collective = sum of all gradients computed.  Integer data,
+    P a power of two: exact.  A process that never missed a result holds w = -sum of the
+    results (lr = 1, mu = 0)."""
+    P, n, T = 4, 6, 40
+    g = _int_gradient(n)
+    produced = np.zeros(n)
+    made = []
+
+    def counted(p, k, w):
+        x = g(p, k, w)
+        made.append((p, k))
+        produced[:] += x
+        return x
+
+    def ms(p, k):                                   # heavy tail: some calls take many rounds
+        return [1.0, 1.3, 0.7, 9.5, 2.2, 0.9, 14.0][(p * 5 + k * 3) % 7]
+    out = ao.simulate(P, n, np.zeros(n, np.float32), 1.0, 0.0, mode, T, ms, counted,
+                      keep_results=True, **kw)
+    assert len(set(made)) == len(made)              # each (process, call) computed once
+    assert max(out["late_calls"]) > 0 and max(out["missed"]) > 0
+    assert len(out["results"]) == T
+    delivered = P * sum(u.astype(np.float64) for u in out["results"])
+    pending = sum((out["send"][p].astype(np.float64) for p in range(P) if out["has_stale"][p]),
+                  np.zeros(n))
+    held = sum((x.astype(np.float64) for x in out["held"].values()), np.zeros(n))
+    assert np.array_equal(delivered + pending + held, produced)
+    for p in range(P):
+        if out["missed"][p] == 0 and out["late_calls"][p] == 0:
+            assert np.array_equal(-out["w"][p].astype(np.float64) * P, delivered)
+
+
+def test_missed_results_make_weights_differ_and_synchronisation_repairs_it():
+    P, n, T = 4, 8, 30
+    rng = np.random.default_rng(1)
+    w0 = rng.standard_normal(n).astype(np.float32)
+
+    def g(p, k, w):
+        return (0.1 * w + 0.01 * ((p + k) % 3 - 1)).astype(np.float32)
+
+    def ms(p, k):
+        return 7.3 if (p == 3 and k % 2 == 0) else 1.0 + 0.1 * p
+    free = ao.simulate(P, n, w0, 0.1, 0.9, "solo", T, ms, g)
+    sync = ao.simulate(P, n, w0, 0.1, 0.9, "solo", T, ms, g, sync_every=T)
+    assert free["missed"][3] > 0
+    spread = lambda ws: max(float(np.max(np.abs(x - np.mean(ws, axis=0)))) for x in ws)  # noqa: E731
+    assert spread(free["w"]) > 1e-4
+    assert spread(sync["w"]) == 0.0 and spread(sync["v"]) == 0.0
+    assert np.allclose(sync["w"][0], np.mean(free["w"], axis=0), atol=1e-6)
+
+
+# ------------------------------------------------------------------ GPU: library loop == oracle loop
+@pytest.fixture(scope="module")
+def asgd():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1908_04207_amd import async_sgd
+    return async_sgd
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("mode,kw,dtype,sync", [
+    ("solo", {}, "f32", 0), ("solo", {}, "bf16", 9), ("majority", {"seed": 77}, "f32", 7),
+    ("quorum", {"quorum": 5}, "f32", 0), ("quorum", {"quorum": 3}, "bf16", 11)])
+def test_library_loop_is_bit_identical_to_the_oracle_loop(asgd, mode, kw, dtype, sync):
+    from paper_1908_04207_amd import binding as eb
+    P, rounds, seed = 8, 60, 4242
+    align = 8 if dtype == "bf16" else 4
+    numel = [301, 7, 0, 2050, 64, 1283]
+    off, cur = [], 0
+    for m in numel:
+        off.append(cur)
+        cur = (cur + m + align - 1) // align * align
+    arena = cur
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    w0 = wg.fill(torch.empty(arena), seed, 0, wg.PARAM_RANK, 0.02)
+
+    def ms(p, k):                                   # Pareto(1.5): long tail, lags of many rounds
+        return wt.compute_times("pareto_1.5", P, seed, k)[p]
+
+    def grad_cpu(p, k):
+        return wg.fill(torch.empty(arena, dtype=tdt), seed, k, p, 1e-3)
+
+    sim = asgd.AsyncEagerSGD(P, off, numel, arena, w0, 0.1, 0.9, mode, kw.get("quorum", 0),
+                             kw.get("seed", 0), sync, eb.BF16 if dtype == "bf16" else eb.F32)
+    res = sim.run(rounds, ms, lambda p, k, w: grad_cpu(p, k).cuda())
+    torch.cuda.synchronize()
+
+    # the oracle works on the concatenation of the buckets (padding carries no data)
+    inside = np.concatenate([np.arange(o, o + m) for o, m in zip(off, numel)])
+    out = ao.simulate(P, len(inside), w0.numpy()[inside], 0.1, 0.9, mode, rounds, ms,
+                      lambda p, k, w: np.ascontiguousarray(as_oracle_grad(grad_cpu(p, k))[inside]),
+                      sync_every=sync, **kw)
+    assert res.nap == out["nap"] and res.late_calls == out["late_calls"]
+    assert res.missed == out["missed"] and res.time_ms == out["time_ms"]
+    assert max(res.late_calls) > 0 and max(res.missed) > 0      # the run did lag
+    assert [sim.k[p] for p in range(P)] == out["calls"]
+    valid = sim.ctx.eager_get_valid(0)
+    assert all(sim.ctx.eager_get_valid(b) == valid for b in range(len(numel)))
+    assert valid == sum(1 << p for p in range(P) if out["has_stale"][p])
+    for p in range(P):
+        assert np.array_equal(bits(sim.w[p].cpu().numpy()[inside]), bits(out["w"][p])), (p, "w")
+        assert np.array_equal(bits(sim.v[p].cpu().numpy()[inside]), bits(out["v"][p])), (p, "v")
+        if (valid >> p) & 1:
+            assert np.array_equal(bits(sim.R[p].cpu().numpy()[inside]), bits(out["send"][p])), (p, "R")
+    if sync:
+        assert len(res.divergence) == rounds and min(res.divergence) == 0.0
+    sim.close()
