@@ -121,6 +121,51 @@ def train(mode: str = "solo", steps: int = 200, P: int = 8, dim: int = 8192,
     return res
 
 
+def train_async(mode: str = "solo", rounds: int = 1200, sync_every: int = 0, P: int = 8,
+                dim: int = 8192, total_batch: int = 2048, lr: float = 0.001, mu: float = 0.9,
+                noise: float = 2.0, seed: int = 20190804, quorum: int = 0,
+                recipe: str = "lognormal_0.3_straggler2x"):
+    """The same problem with a clock and a weight view per process (async_sgd.AsyncEagerSGD):
+    compute times from a heavy-tailed recipe carry over from call to call, so processes lag
+    by several rounds, miss results and drift apart; every `sync_every` rounds the models
+    are averaged (Section 5, last paragraph).  Each process computes its gradients from ITS
+    weights.  Returns (AsyncResult, validation MSE of the averaged model, largest distance of
+    a weight view from the average).  The learning rate is smaller than in `train`: gradients
+    that arrive several rounds late and weight views that drift apart make the larger one
+    unstable without synchronisation (with it, 0.01 works as well)."""
+    import torch
+    from workloads import times as wt
+    from .async_sgd import AsyncEagerSGD
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n = dim + 1
+    arena = (n + 3) // 4 * 4
+    a_true = torch.randn(dim, device=dev, generator=gen)
+    Xv = torch.randn(4096, dim, device=dev, generator=gen)
+    yv = Xv @ a_true + noise * torch.randn(4096, device=dev, generator=gen)
+    bs = total_batch // P
+
+    def gradient(p, k, w):
+        X = torch.randn(bs, dim, device=dev, generator=gen)
+        y = X @ a_true + noise * torch.randn(bs, device=dev, generator=gen)
+        err = X @ w[:dim] + w[dim] - y
+        g = torch.zeros(arena, device=dev)
+        g[:dim] = (2.0 / bs) * (X.t() @ err)
+        g[dim] = 2.0 * err.mean()
+        return g
+
+    sim = AsyncEagerSGD(P, [0], [n], arena, torch.zeros(arena), lr, mu, mode, quorum, seed,
+                        sync_every)
+    res = sim.run(rounds, lambda p, k: 400.0 * wt.compute_times(recipe, P, seed, k)[p], gradient)
+    stack = torch.stack(sim.w)
+    mean = stack.mean(0)
+    loss = float(((Xv @ mean[:dim] + mean[dim] - yv) ** 2).mean())
+    spread = float((stack - mean).abs().max())
+    sim.close()
+    return res, loss, spread
+
+
 def main() -> None:
     import argparse
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
@@ -130,7 +175,19 @@ def main() -> None:
                     help="the spectrum between solo (k = 1) and synchronous SGD (k = P) that the "
                          "paper's conclusions propose: k-of-P rounds for every k, 300 ms delay on "
                          "two random ranks per step")
+    ap.add_argument("--lagging", action="store_true",
+                    help="a clock and a weight view per process, heavy-tailed compute times: "
+                         "lag of several rounds, with and without periodic model synchronisation")
     a = ap.parse_args()
+    if a.lagging:
+        for mode, kw in (("solo", {}), ("majority", {}), ("quorum", {"quorum": 4})):
+            for sync in (0, 10):
+                r, loss, spread = train_async(mode, max(a.steps, 1200), sync, **kw)
+                print(f"{mode:9s} sync every {sync:2d}: {r.rounds} rounds in {r.time_ms / 1e3:6.1f} s, "
+                      f"NAP {sum(r.nap) / len(r.nap):4.2f}, late calls {sum(r.late_calls)}, results "
+                      f"missed {sum(r.missed)}, views differ by {spread:.2e}, validation MSE of the "
+                      f"mean model {loss:.3f}")
+        return
     if a.quorum_sweep:
         P = 8
         runs = [train("quorum", a.steps, P=P, quorum=k, delay_ms=300.0, delayed_ranks=2)

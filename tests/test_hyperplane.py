@@ -83,6 +83,22 @@ def test_quorum_spectrum_trades_time_for_freshness(hp):
         assert r.val_loss[-1] < 0.05 * r.val_loss[0]
 
 
+@pytest.mark.gpu
+def test_lagging_processes_drift_apart_and_synchronisation_repairs_it(hp):
+    """Section 5, last paragraph, on the hyperplane problem with a clock and a weight view per
+    process: processes that lag miss results, their weights differ and the accuracy suffers,
+    more with solo than with majority; periodic model synchronisation removes the effect."""
+    solo_free, loss_solo_free, spread_solo_free = hp.train_async("solo", 1200, 0)
+    solo_sync, loss_solo_sync, spread_solo_sync = hp.train_async("solo", 1200, 10)
+    maj_free, loss_maj_free, spread_maj_free = hp.train_async("majority", 1200, 0)
+    assert sum(solo_free.missed) > sum(maj_free.missed) > 0
+    assert spread_solo_free > spread_maj_free > 0.0 and spread_solo_sync == 0.0
+    assert solo_free.nap == solo_sync.nap and solo_free.time_ms == solo_sync.time_ms
+    assert loss_solo_sync < 0.7 * loss_solo_free
+    assert loss_maj_free < 0.7 * loss_solo_free
+    assert 3.6 < loss_solo_sync < 6.0                  # noise floor 4.0
+
+
 def test_time_model_reproduces_the_reported_speedups():
     from harness import paper_values
     from paper_1908_04207_amd import hyperplane as hp
