@@ -22,7 +22,9 @@
  *   - "device" pointers are HIP device memory owned by the caller; the library never
  *     allocates, frees or clears them.  "host" pointers are ordinary host memory.
  *   - Kernels are enqueued on the caller's stream (a hipStream_t passed as void*,
- *     NULL = the default stream).  No call synchronises the device.
+ *     NULL = the default stream).  No call synchronises the device, allocates or clears
+ *     device memory, so a sequence of calls can be captured in a HIP graph; the first use
+ *     of a kernel sets a function attribute, so run one round eagerly before capturing.
  *   - Arena layout: each of G_p, R_p, w, v, recv is one flat array per process in
  *     which bucket b occupies elements [bucket_offset[b], bucket_offset[b] +
  *     bucket_numel[b]).  Bucket starts are multiples of 16 bytes of the gradient type
