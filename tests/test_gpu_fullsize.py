@@ -110,3 +110,41 @@ def test_full_size_sampled(eb, k, steps, order, launch):
                 tol = 1e-2 if cfg.grad_dtype == "bf16" else 1e-6
                 assert normwise(got[name], want[name]) <= tol, (cfg.name, t, name)
     ctx.close()
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_full_size_bucket_statistics(eb, k):
+    """The per-bucket sums at full size (hundreds of thousands of wavefront records, buckets
+    from 64 to 16.8 M elements) against torch's own fp64 reductions of the receive buffer and
+    of the parameters on the GPU: a property that holds at any size, checked with a library
+    routine.  (Element-wise parity of the same rounds is covered by the sampled test.)"""
+    cfg = shapes.config(k)
+    bt = cfg.buckets
+    dev = torch.device("cuda:0")
+    n = bt.arena_numel
+    ctx = eb.Context(cfg.P, bt.offset, bt.numel, eb.F32, eb.ORDER_FIXED)
+    G = [torch.empty(n, device=dev) for _ in range(cfg.P)]
+    R = [torch.empty(n, device=dev) for _ in range(cfg.P)]
+    w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
+    v = torch.zeros(n, device=dev)
+    recv = torch.empty(n, device=dev)
+    stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
+    nbytes = ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ctx.eager_stats_attach(stats, ws, nbytes)
+    for t in range(3):
+        print(f"{cfg.name} statistics step {t}", flush=True)
+        plan = plan_for(eb, cfg, t)
+        for p in range(cfg.P):
+            wg.fill(G[p], cfg.seed, t, p, cfg.grad_sigma)
+        w_before = w.clone()
+        ctx.eager_partial_allreduce(plan, G, R, recv=recv, opt=(w, v, cfg.lr, cfg.mu))
+        torch.cuda.synchronize()
+        got = stats.cpu().numpy().reshape(-1, 4)
+        for b, (o, m) in enumerate(zip(bt.offset, bt.numel)):
+            ssu = float(recv[o:o + m].double().square().sum())
+            ssw = float(w_before[o:o + m].double().square().sum())
+            assert abs(got[b, 0] - ssu) <= 1e-9 * max(ssu, 1e-300), (t, b, got[b, 0], ssu)
+            assert abs(got[b, 1] - ssw) <= 1e-9 * max(ssw, 1e-300), (t, b, got[b, 1], ssw)
+            assert got[b, 2].view(np.uint64) == 0
+    ctx.close()
