@@ -464,6 +464,72 @@ def test_round_captured_in_a_graph(eb):
         _ = (pair.w * 2).sum().item()                  # unrelated eager work and a sync
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_nothing_is_written_outside_the_buffers(eb, dtype):
+    """All arenas carved out of one allocation with guard zones between them; after rounds in
+    every launch form, stashes and statistics, the guards still hold their pattern: no kernel
+    stores outside [offset[0], end of the last bucket) of a buffer it is given."""
+    P = 5
+    align = 8 if dtype == "bf16" else 4
+    numel = [3, 1021, 0, 4099, 7]
+    off, cur = [], 0
+    for m in numel:
+        off.append(cur)
+        cur = (cur + m + align - 1) // align * align
+    arena = off[-1] + numel[-1]                      # no slack after the last element
+    gdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gsize = 2 if dtype == "bf16" else 4
+    guard = 256                                      # bytes
+    names = [("G", p, gsize) for p in range(P)] + [("R", p, 4) for p in range(P)] + \
+            [("w", 0, 4), ("v", 0, 4), ("recv", 0, 4)]
+    total, place = guard, {}
+    for name, p, size in names:
+        place[(name, p)] = total
+        total += (arena * size + 15) // 16 * 16 + guard
+    pool = torch.full((total,), 0xA5, dtype=torch.uint8, device="cuda")
+
+    def view(name, p, dt, size):
+        o = place[(name, p)]
+        return pool[o:o + arena * size].view(dt)
+    G = [view("G", p, gdt, gsize) for p in range(P)]
+    R = [view("R", p, torch.float32, 4) for p in range(P)]
+    w, v, recv = (view(x, 0, torch.float32, 4) for x in ("w", "v", "recv"))
+    for t_ in G + R + [w, v, recv]:
+        t_.zero_()
+    inside = torch.zeros(total, dtype=torch.bool, device="cuda")
+    for name, p, size in names:
+        inside[place[(name, p)]:place[(name, p)] + arena * size] = True
+    rng = np.random.default_rng(3)
+    nb = len(numel)
+    for launch in ({}, {"split": 2}, {"split": 1, "chunk": 8}, {"compact": 0, "unroll": 2},
+                   {"block": 256, "blocks_per_cu": 1, "xcd_map": 1}):
+        ctx = eb.Context(P, off, numel, eb.BF16 if dtype == "bf16" else eb.F32, eb.ORDER_FIXED)
+        for key, val in launch.items():
+            ctx.eager_set_launch(key, val)
+        use_stats = launch.get("compact", 1) == 1 and launch.get("chunk", 0) in (0, 16)
+        if use_stats:
+            stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+            nbytes = ctx.eager_stats_workspace_bytes()
+            ws = torch.empty(nbytes + 64, dtype=torch.uint8, device="cuda")
+            ws[nbytes:] = 0x5A
+            ctx.eager_stats_attach(stats, ws, nbytes)
+        for t in range(4):
+            state = rng.integers(0, 3, P)
+            state[t % P] = 0
+            mask = sum(1 << p for p in range(P) if state[p] == 0)
+            absent = sum(1 << p for p in range(P) if state[p] == 2)
+            ctx.eager_partial_allreduce_lagging(eb.make_plan(eb.SOLO, P, t, mask), absent, G, R,
+                                                recv=recv, opt=(w, v, 0.1, 0.9))
+            ctx.eager_stash(int(rng.integers(0, P)), G[0], R[int(rng.integers(0, P))])
+        ctx.eager_partial_allreduce(eb.make_plan(eb.MAJORITY, P, 9, 1), G, R, recv=recv)
+        ctx.eager_sgd_step(recv, (w, v, 0.1, 0.9))
+        torch.cuda.synchronize()
+        assert bool((pool[~inside] == 0xA5).all()), f"guard zone overwritten with launch {launch}"
+        if use_stats:
+            assert bool((ws[nbytes:] == 0x5A).all()), "statistics workspace overrun"
+        ctx.close()
+
+
 def test_nonfinite_and_denormal_values(eb):
     """Inf/NaN gradients propagate as in the oracle; denormals are kept (no flush to
     zero), bit for bit."""
