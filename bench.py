@@ -315,9 +315,10 @@ def main() -> int:
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(wall / a.steps * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if cfg.grad_dtype == "f32" else "bf16 gradients, f32 accumulation/state",
+        "dtype": "f32",          # the arithmetic type (sums, average, update rule); gradients
+                                 # may be stored as bf16, see config.grad_dtype
         "data": "synthetic",
-        "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode,
+        "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode, "grad_dtype": cfg.grad_dtype,
                    "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
                    "order": a.order, "launch": launch, "stagger": a.stagger,
                    "bucket_stats": a.stats, "unfused": a.unfused},
