@@ -191,6 +191,24 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update,
                    const eager_opt *opt, void *stream);
 
 /*
+ * A weight view per process (processes that lag by more than one round apply only the
+ * results they see, so their weights differ; Section 5, last paragraph).
+ * eager_sgd_step_views applies the update rule with one read of `update` to each of the
+ * n_views (1..64) parameter/momentum pairs (host arrays of device pointers, fp32 arenas,
+ * 16-byte aligned, pairwise distinct) - the processes that see this result.
+ * eager_average_views is the periodic model synchronisation: every listed array is
+ * replaced by the average of all of them (sum in the order given starting from +0.0f, times
+ * 1/n_views in fp32: the arithmetic of a round in which everybody is on time); call it once
+ * for the parameter views and once for the momentum views.
+ * Errors: EINVAL (NULL, alignment, n_views, range, the same buffer listed twice), EDEVICE.
+ */
+int eager_sgd_step_views(eager_ctx *ctx, int b0, int b1, const float *update, int n_views,
+                         float *const *params, float *const *momentum, float lr, float mu,
+                         void *stream);
+int eager_average_views(eager_ctx *ctx, int b0, int b1, int n_views, float *const *views,
+                        void *stream);
+
+/*
  * Variants of the update rule U (the paper leaves U generic, Algorithm 2 line 7).  They apply
  * to every later fused round and eager_sgd_step of this context:
  *     g  = u + weight_decay * w        (skipped when weight_decay == 0)

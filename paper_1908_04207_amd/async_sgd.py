@@ -26,9 +26,9 @@ Every `sync_every` rounds the models are synchronised: every w_p and v_p is repl
 average over the processes ("we periodically synchronize the models across all processes").
 
 All arithmetic runs in the library: the round (`eager_partial_allreduce_lagging`, receive
-buffer only), the update rule per weight view (`eager_sgd_step`), the stash (`eager_stash`)
-and the model average (a full allreduce of the P weight arrays through a second context
-whose send buffers stay empty).  This module is the event loop and the bookkeeping.
+buffer only), the update rule on the weight views of the processes that see a result
+(`eager_sgd_step_views`, one kernel), the stash (`eager_stash`) and the model average
+(`eager_average_views`).  This module is the event loop and the bookkeeping.
 
 Readings taken here (the paper gives no detail): simultaneous arrivals are handled together
 (late calls first, by rank; the others all count as arrived); a model synchronisation takes
@@ -66,20 +66,16 @@ class AsyncEagerSGD:
         self.mode, self.quorum, self.seed, self.sync_every = mode, quorum, seed, sync_every
         dev = torch.device("cuda:0")
         self.ctx = eb.Context(P, bucket_offset, bucket_numel, grad_dtype, eb.ORDER_FIXED)
-        # model averaging = a full allreduce of fp32 arrays; its own context: no send buffers
-        self.avg = eb.Context(P, bucket_offset, bucket_numel, eb.F32, eb.ORDER_FIXED)
         self.w = [w0.to(dev).clone() for _ in range(P)]
         self.v = [torch.zeros(arena_numel, device=dev) for _ in range(P)]
         self.R = [torch.zeros(arena_numel, device=dev) for _ in range(P)]
         self.recv = torch.zeros(arena_numel, device=dev)
-        self.mean = torch.zeros(arena_numel, device=dev)
         self.r = 0                              # rounds executed
         self.k = [0] * P                        # calls made
         self.T = [0.0] * P                      # time of the next call
         self.seen = [-1] * P                    # last result applied
         self.waiting: List[int] = []
         self.held = {}                          # gradients of the waiting processes
-        self.avg_step = 0
         self.track_divergence = track_divergence
         self.res = AsyncResult(calls=[0] * P, late_calls=[0] * P, missed=[0] * P)
 
@@ -96,21 +92,18 @@ class AsyncEagerSGD:
             return len(self.waiting) >= self.quorum
         raise ValueError(self.mode)
 
-    def _apply(self, p: int) -> None:
-        """Process p applies the result in the receive buffer (the latest round's)."""
-        self.ctx.eager_sgd_step(self.recv, (self.w[p], self.v[p], self.lr, self.mu))
-        self.res.missed[p] += self.r - 1 - self.seen[p] - 1
-        self.seen[p] = self.r - 1
+    def _apply(self, procs: Sequence[int]) -> None:
+        """The listed processes apply the result in the receive buffer (the latest round's)
+        to their own weights: one kernel, one read of the result."""
+        self.ctx.eager_sgd_step_views(self.recv, [self.w[p] for p in procs],
+                                      [self.v[p] for p in procs], self.lr, self.mu)
+        for p in procs:
+            self.res.missed[p] += self.r - 1 - self.seen[p] - 1
+            self.seen[p] = self.r - 1
 
     def _synchronise(self) -> None:
-        full = (1 << self.P) - 1
-        for views in (self.w, self.v):
-            plan = eb.make_plan(eb.QUORUM, self.P, self.avg_step, full)
-            self.avg_step += 1
-            # everybody "on time", send buffers empty: the buffers passed as such are never touched
-            self.avg.eager_partial_allreduce(plan, views, [self.mean] * self.P, recv=self.mean)
-            for x in views:
-                x.copy_(self.mean)
+        self.ctx.eager_average_views(self.w)
+        self.ctx.eager_average_views(self.v)
 
     def run(self, rounds: int, compute_ms: Callable[[int, int], float],
             gradient: Callable[[int, int, object], object]) -> AsyncResult:
@@ -128,7 +121,7 @@ class AsyncEagerSGD:
             for p in [q for q in arrived if self.k[q] < self.r]:           # late calls
                 self.ctx.eager_stash(p, gradient(p, self.k[p], self.w[p]), self.R[p])
                 if self.seen[p] < self.r - 1:
-                    self._apply(p)
+                    self._apply([p])
                 self.res.calls[p] += 1
                 self.res.late_calls[p] += 1
                 self.k[p] += 1
@@ -151,8 +144,8 @@ class AsyncEagerSGD:
             self.ctx.eager_partial_allreduce_lagging(plan, absent, grads, self.R, recv=self.recv)
             self.r += 1
             self.res.nap.append(len(self.waiting))
+            self._apply(self.waiting)
             for p in self.waiting:
-                self._apply(p)
                 self.k[p] += 1
                 self.T[p] = now + compute_ms(p, self.k[p])
             self.waiting, self.held = [], {}
@@ -166,4 +159,3 @@ class AsyncEagerSGD:
 
     def close(self) -> None:
         self.ctx.close()
-        self.avg.close()

@@ -25,7 +25,8 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_set_update_rule", "eager_stats_workspace_bytes",
+    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_views",
+    "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
 )
@@ -85,6 +86,9 @@ def _load() -> ctypes.CDLL:
         ctypes.POINTER(Opt), vp]
     lib.eager_stash.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
+    lib.eager_sgd_step_views.argtypes = [vp, i32, i32, vp, i32, ctypes.POINTER(vp),
+                                         ctypes.POINTER(vp), ctypes.c_float, ctypes.c_float, vp]
+    lib.eager_average_views.argtypes = [vp, i32, i32, i32, ctypes.POINTER(vp), vp]
     lib.eager_get_valid.argtypes = [vp, i32, ctypes.POINTER(u64)]
     lib.eager_set_valid.argtypes = [vp, i32, u64]
     lib.eager_set_launch.argtypes = [vp, ctypes.c_char_p, i32]
@@ -241,6 +245,18 @@ class Context:
         o = Opt(_ptr(params), _ptr(momentum), lr, mu)
         self._check(lib.eager_sgd_step(self._h, b0, b1, _ptr(update), ctypes.byref(o),
                                        _stream(stream)), "eager_sgd_step")
+
+    def eager_sgd_step_views(self, update, params, momentum, lr: float, mu: float, b0: int = 0,
+                             b1: Optional[int] = None, stream=None) -> None:
+        b1 = self.n_buckets if b1 is None else b1
+        self._check(lib.eager_sgd_step_views(self._h, b0, b1, _ptr(update), len(params),
+                                             self.pointers(params), self.pointers(momentum),
+                                             lr, mu, _stream(stream)), "eager_sgd_step_views")
+
+    def eager_average_views(self, views, b0: int = 0, b1: Optional[int] = None, stream=None) -> None:
+        b1 = self.n_buckets if b1 is None else b1
+        self._check(lib.eager_average_views(self._h, b0, b1, len(views), self.pointers(views),
+                                            _stream(stream)), "eager_average_views")
 
     def eager_get_valid(self, bucket: int) -> int:
         v = ctypes.c_uint64()

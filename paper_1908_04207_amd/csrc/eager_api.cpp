@@ -457,6 +457,67 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const ea
     return EAGER_OK;
 }
 
+namespace {
+int fill_views(eager_ctx *ctx, eager::ViewsArgs &a, int b0, int b1, int n_views,
+               float *const *params, float *const *momentum)
+{
+    if (n_views < 1 || n_views > EAGER_MAX_P)
+        return fail(ctx, EAGER_EINVAL, "n_views must be 1..%d", EAGER_MAX_P);
+    if (!params) return fail(ctx, EAGER_EINVAL, "params must not be NULL");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    std::memset(&a, 0, sizeof a);
+    for (int p = 0; p < n_views; ++p) {
+        if (!params[p] || !aligned16(params[p]) ||
+            (momentum && (!momentum[p] || !aligned16(momentum[p]))))
+            return fail(ctx, EAGER_EINVAL, "view %d is NULL or not 16-byte aligned", p);
+        for (int q = 0; q < p; ++q)
+            if (params[q] == params[p] || (momentum && momentum[q] == momentum[p]))
+                return fail(ctx, EAGER_EINVAL, "views %d and %d are the same buffer", q, p);
+        a.w[p] = params[p];
+        a.v[p] = momentum ? momentum[p] : nullptr;
+    }
+    a.n_views = n_views;
+    a.e0 = ctx->offset[b0];
+    a.n = ctx->offset[b1 - 1] + ctx->numel[b1 - 1] - ctx->offset[b0];
+    return EAGER_OK;
+}
+}  // namespace
+
+int eager_sgd_step_views(eager_ctx *ctx, int b0, int b1, const float *update, int n_views,
+                         float *const *params, float *const *momentum, float lr, float mu,
+                         void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!update || !aligned16(update) || !momentum)
+        return fail(ctx, EAGER_EINVAL, "update and momentum must not be NULL, update 16-byte aligned");
+    eager::ViewsArgs a;
+    if (int st = fill_views(ctx, a, b0, b1, n_views, params, momentum)) return st;
+    a.u = update;
+    a.neg_lr = -lr;
+    a.mu = mu;
+    a.wd = ctx->weight_decay;
+    a.nesterov = ctx->nesterov;
+    hipError_t he = eager::launch_views_sgd(a, ctx->fast, ctx->launch, static_cast<hipStream_t>(stream));
+    if (he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "views kernel launch failed: %s", hipGetErrorString(he));
+    ctx->err.clear();
+    return EAGER_OK;
+}
+
+int eager_average_views(eager_ctx *ctx, int b0, int b1, int n_views, float *const *views,
+                        void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    eager::ViewsArgs a;
+    if (int st = fill_views(ctx, a, b0, b1, n_views, views, nullptr)) return st;
+    a.inv_views = 1.0f / static_cast<float>(n_views);
+    hipError_t he = eager::launch_views_average(a, ctx->launch, static_cast<hipStream_t>(stream));
+    if (he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "views kernel launch failed: %s", hipGetErrorString(he));
+    ctx->err.clear();
+    return EAGER_OK;
+}
+
 int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask)
 {
     if (!ctx || !valid_mask || bucket < 0 || bucket >= ctx->n_buckets) return EAGER_EINVAL;

@@ -117,6 +117,19 @@ struct StashArgs {
     int accumulate;              // 1: the send buffer holds an undelivered gradient
 };
 
+// Several weight views at once (a weight view per process, for processes that lag by more
+// than one round): the update rule applied to every listed view from one read of u, or
+// every view replaced by the average of all of them.
+struct ViewsArgs {
+    float *w[kMaxP];             // parameter views
+    float *v[kMaxP];             // momentum views (update rule only)
+    const float *u;              // averaged update (update rule only)
+    int n_views;
+    long long e0, n;
+    float neg_lr, mu, wd, inv_views;
+    int nesterov;
+};
+
 struct SgdArgs {
     const float *u;
     float *w;
@@ -154,6 +167,8 @@ hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
 long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch
 int slot_tail(long long n, bool bf16);                       // elements of its ragged tail
 hipError_t launch_stash(const StashArgs &a, bool bf16, hipStream_t stream);
+hipError_t launch_views_sgd(const ViewsArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
+hipError_t launch_views_average(const ViewsArgs &a, const Launch &cfg, hipStream_t stream);
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);

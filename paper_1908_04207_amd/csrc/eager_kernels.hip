@@ -879,6 +879,120 @@ __global__ __launch_bounds__(64) void stash_kernel(const StashArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Weight views (one per process).  Both kernels: a lane owns 4 elements, the pointer table is
+// read from the kernel-argument segment, views are taken in chunks whose loads are all issued
+// before the first use, the last chunk has its exact size.
+typedef const ViewsArgs __attribute__((address_space(4))) KViewsArgs;
+
+// the update rule on C views from one value of u: 2C loads, then the arithmetic, then 2C stores
+template <bool FAST, int C>
+__device__ __forceinline__ void views_sgd_chunk(KViewsArgs &a, int p0, long long e, f32x4 u)
+{
+    f32x4 wo[C], vo[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        vo[j] = ld_f4<true>(a.v[p0 + j] + e);
+        wo[j] = ld_f4<true>(a.w[p0 + j] + e);
+    }
+    const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+    f32x4 vn[C], wn[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) update_rule<FAST>(rule, u, vo[j], wo[j], vn[j], wn[j]);
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        st_f4<true>(a.v[p0 + j] + e, vn[j]);
+        st_f4<true>(a.w[p0 + j] + e, wn[j]);
+    }
+}
+template <bool FAST, int R>
+__device__ __forceinline__ void views_sgd_rest(KViewsArgs &a, int p0, int rem, long long e, f32x4 u)
+{
+    if constexpr (R >= 1) {
+        if (rem == R) views_sgd_chunk<FAST, R>(a, p0, e, u);
+        else views_sgd_rest<FAST, R - 1>(a, p0, rem, e, u);
+    }
+}
+
+template <bool FAST>
+__global__ __launch_bounds__(64) void views_sgd_kernel(const ViewsArgs)
+{
+    KViewsArgs &a = kernarg<ViewsArgs>();
+    constexpr int CH = 8;
+    const long long nvec = a.n / 4;
+    const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (vi < nvec) {
+        const long long e = a.e0 + vi * 4;
+        const f32x4 u = ld_f4<true>(a.u + e);
+        const int V = a.n_views;
+#pragma unroll
+        for (int c = 0; c < kMaxP / CH; ++c)
+            if ((c + 1) * CH <= V) views_sgd_chunk<FAST, CH>(a, c * CH, e, u);
+        views_sgd_rest<FAST, CH - 1>(a, V / CH * CH, V % CH, e, u);
+    }
+    const long long rem = a.n - nvec * 4;
+    if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem) {
+        const long long i = a.e0 + nvec * 4 + threadIdx.x;
+        const UpdateRule rule = {a.neg_lr, a.mu, a.wd, a.nesterov};
+        const float u = a.u[i];
+        for (int p = 0; p < a.n_views; ++p) {
+            float v = a.v[p][i], w = a.w[p][i];
+            update_rule_scalar(rule, u, v, w);
+            a.v[p][i] = v;
+            a.w[p][i] = w;
+        }
+    }
+}
+
+// model synchronisation: every view <- (sum of the views in ascending order from +0.0f) * 1/V,
+// the arithmetic of a round in which everybody is on time with an empty send buffer
+template <int C>
+__device__ __forceinline__ f32x4 views_sum_chunk(KViewsArgs &a, int p0, long long e, f32x4 s)
+{
+    f32x4 x[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) x[j] = ld_f4<true>(a.w[p0 + j] + e);
+#pragma unroll
+    for (int j = 0; j < C; ++j) s = s + x[j];
+    return s;
+}
+template <int R>
+__device__ __forceinline__ f32x4 views_sum_rest(KViewsArgs &a, int p0, int rem, long long e, f32x4 s)
+{
+    if constexpr (R >= 1) {
+        if (rem == R) return views_sum_chunk<R>(a, p0, e, s);
+        return views_sum_rest<R - 1>(a, p0, rem, e, s);
+    }
+    return s;
+}
+
+__global__ __launch_bounds__(64) void views_average_kernel(const ViewsArgs)
+{
+    KViewsArgs &a = kernarg<ViewsArgs>();
+    constexpr int CH = 16;
+    const long long nvec = a.n / 4;
+    const long long vi = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const int V = a.n_views;
+    if (vi < nvec) {
+        const long long e = a.e0 + vi * 4;
+        f32x4 s = (f32x4)(0.0f);
+#pragma unroll
+        for (int c = 0; c < kMaxP / CH; ++c)
+            if ((c + 1) * CH <= V) s = views_sum_chunk<CH>(a, c * CH, e, s);
+        s = views_sum_rest<CH - 1>(a, V / CH * CH, V % CH, e, s);
+        const f32x4 mean = s * a.inv_views;
+        for (int p = 0; p < V; ++p) st_f4<true>(a.w[p] + e, mean);
+    }
+    const long long rem = a.n - nvec * 4;
+    if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem) {
+        const long long i = a.e0 + nvec * 4 + threadIdx.x;
+        float s = 0.0f;
+        for (int p = 0; p < V; ++p) s = s + a.w[p][i];
+        const float mean = s * a.inv_views;
+        for (int p = 0; p < V; ++p) a.w[p][i] = mean;
+    }
+}
+
 template <bool FAST>
 __global__ __launch_bounds__(256) void sgd_kernel(const SgdArgs a)
 {
@@ -939,6 +1053,11 @@ constexpr long long kMaxGridThreads = 1ll << 31;
 
 // Parameters and momentum above this size are streamed past the caches (see slot_vectors).
 constexpr long long kStateCacheBytes = 256ll << 20;
+
+// Resident wavefronts per CU of the weight-view kernels when the caller leaves it open
+// (measured, 8 views of 2^26 elements: update 6.36 TB/s with 3, 5.68 uncapped; average 6.50
+// with 4, 5.82 uncapped).
+constexpr int kViewsSgdWaves = 3, kViewsAverageWaves = 4;
 
 // Resident workgroups per CU when the caller leaves the choice to the library: measured
 // optima of the rank-chunk kernel with 64-thread workgroups for 1, 2 and 4 chunks of 8.
@@ -1230,6 +1349,34 @@ hipError_t launch_stash(const StashArgs &a, bool bf16, hipStream_t stream)
     if (bf16) hipLaunchKernelGGL(stash_kernel<true>, dim3(static_cast<unsigned>(g)), dim3(64), 0, stream, a);
     else hipLaunchKernelGGL(stash_kernel<false>, dim3(static_cast<unsigned>(g)), dim3(64), 0, stream, a);
     return hipGetLastError();
+}
+
+namespace {
+template <typename K>
+hipError_t launch_views(K kernel, const ViewsArgs &a, const Launch &cfg, int auto_waves,
+                        hipStream_t stream)
+{
+    if (a.n <= 0 || a.n_views <= 0) return hipSuccess;
+    long long g = (a.n / 4 + 63) / 64;
+    if (g < 1) g = 1;
+    if (g * 64 > kMaxGridThreads) return hipErrorInvalidValue;    // these kernels do not stride
+    Launch l = cfg;
+    l.block = 64;
+    // half of the traffic is stores: few wavefronts per CU, as for the rounds
+    const int bpc = cfg.blocks_per_cu == 0 ? auto_waves : cfg.blocks_per_cu;
+    return launch_capped(kernel, a, bpc, l, static_cast<unsigned>(g), stream);
+}
+}  // namespace
+
+hipError_t launch_views_sgd(const ViewsArgs &a, bool fast, const Launch &cfg, hipStream_t stream)
+{
+    return fast ? launch_views(views_sgd_kernel<true>, a, cfg, kViewsSgdWaves, stream)
+                : launch_views(views_sgd_kernel<false>, a, cfg, kViewsSgdWaves, stream);
+}
+
+hipError_t launch_views_average(const ViewsArgs &a, const Launch &cfg, hipStream_t stream)
+{
+    return launch_views(views_average_kernel, a, cfg, kViewsAverageWaves, stream);
 }
 
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream)

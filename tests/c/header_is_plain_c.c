@@ -26,6 +26,9 @@ int (*const p_lagging)(eager_ctx *, const eager_plan *, uint64_t, int, int, cons
                        float *const *, float *, const eager_opt *, void *) = eager_partial_allreduce_lagging;
 int (*const p_stash)(eager_ctx *, int, int, int, const void *, float *, void *) = eager_stash;
 int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
+int (*const p_views)(eager_ctx *, int, int, const float *, int, float *const *, float *const *, float,
+                     float, void *) = eager_sgd_step_views;
+int (*const p_average)(eager_ctx *, int, int, int, float *const *, void *) = eager_average_views;
 int (*const p_rule)(eager_ctx *, float, int) = eager_set_update_rule;
 int (*const p_stats_bytes)(const eager_ctx *, int64_t *) = eager_stats_workspace_bytes;
 int (*const p_stats_attach)(eager_ctx *, eager_bucket_stats *, void *, int64_t, void *) = eager_stats_attach;

@@ -365,6 +365,47 @@ def test_lagging_processes_and_stashed_gradients(eb, dtype, launch, order):
     assert e.value.status == eb.EINVAL
 
 
+@pytest.mark.parametrize("V", [1, 3, 8, 9, 17, 64])
+def test_weight_views_update_and_average(eb, V):
+    """The update rule on V weight views from one read of the result, and the model average of
+    V views, against the oracle's per-view update and its full round with empty send buffers;
+    ragged sizes, a bucket range, Nesterov + weight decay; bitwise."""
+    from oracle import eager_oracle as eo
+    numel = [1029, 3, 0, 2050]
+    off = [0, 1032, 1036, 1036]
+    arena = 1036 + 2050
+    rng = np.random.default_rng(V)
+    ctx = eb.Context(2, off, numel, eb.F32, eb.ORDER_FIXED)
+    ctx.eager_set_update_rule(0.01, True)
+    hw = [rng.standard_normal(arena).astype(np.float32) for _ in range(V)]
+    hv = [rng.standard_normal(arena).astype(np.float32) for _ in range(V)]
+    hu = rng.standard_normal(arena).astype(np.float32)
+    w = [torch.from_numpy(x.copy()).cuda() for x in hw]
+    v = [torch.from_numpy(x.copy()).cuda() for x in hv]
+    u = torch.from_numpy(hu).cuda()
+    ctx.eager_sgd_step_views(u, w, v, 0.05, 0.9)
+    ctx.eager_average_views(v, 1, 4)                 # buckets 1..3 only
+    torch.cuda.synchronize()
+    for p in range(V):
+        for o, m in zip(off, numel):
+            eo.sgd_f32(hu[o:o + m], hw[p][o:o + m], hv[p][o:o + m], 0.05, 0.9, wd=0.01, nesterov=True)
+    for o, m in list(zip(off, numel))[1:]:
+        mean = np.zeros(m, dtype=np.float32)
+        eo.round_f32([x[o:o + m] for x in hv], [np.zeros(m, np.float32) for _ in range(V)], 0,
+                     (1 << V) - 1, None, None, 0.0, 0.0, recv=mean)
+        for x in hv:
+            x[o:o + m] = mean
+    inside = np.concatenate([np.arange(o, o + m) for o, m in zip(off, numel)])
+    from harness import bits
+    for p in range(V):
+        assert np.array_equal(bits(w[p].cpu().numpy()[inside]), bits(hw[p][inside])), (V, p, "w")
+        assert np.array_equal(bits(v[p].cpu().numpy()[inside]), bits(hv[p][inside])), (V, p, "v")
+    with pytest.raises(eb.EagerError) as e:          # the same buffer listed twice
+        ctx.eager_average_views([w[0], w[0]])
+    assert e.value.status == eb.EINVAL
+    ctx.close()
+
+
 def test_bucket_ranges_on_concurrent_streams(eb):
     """Layer-wise reductions are independent (Section 3): the buckets of one round issued as
     ranges on three streams at once, last layers first, give the bits of one whole-range
