@@ -177,6 +177,50 @@ void eager_oracle_sgd_ex(int64_t n, const float *u, float *w, float *v, float lr
         update_rule(u[i], &w[i], &v[i], lr, mu, wd, nesterov);
 }
 
+/*
+ * The update rule with a rate per layer (bucket), one more instance of the generic U of
+ * Algorithm 2, line 7: layer-wise adaptive rate scaling as published by You, Gitman and
+ * Ginsburg (2017), the large-batch recipe behind the work the paper points to in
+ * Section 7.3 for batch sizes that need tuned rates.  For a bucket with averaged update u
+ * and parameters w (both before the step), over the finite elements only:
+ *
+ *     rate = trust * ||w|| / (||u|| + wd * ||w|| + eps)     if ||w|| > 0 and ||u|| > 0
+ *          = 1                                              otherwise (e.g. biases at zero)
+ *
+ * norms from fp64 sums of squares in index order, the rate computed in fp64 and rounded to
+ * fp32 once.  Then per element
+ *
+ *     g = rate * (u + wd * w);  v' = mu * v + g;  step = nesterov ? g + mu * v' : v';
+ *     w' = w - lr * step
+ *
+ * (the scaled gradient enters the momentum, as in the publication).  Returns the rate.
+ */
+float eager_oracle_sgd_lars(int64_t n, const float *u, float *w, float *v, float lr, float mu,
+                            float wd, int nesterov, float trust, float eps)
+{
+    double ssu = 0.0, ssw = 0.0, nu, nw;
+    float rate = 1.0f;
+    int64_t i;
+    for (i = 0; i < n; ++i) {
+        if (isfinite(u[i]))
+            ssu += (double)u[i] * (double)u[i];
+        if (isfinite(w[i]))
+            ssw += (double)w[i] * (double)w[i];
+    }
+    nu = sqrt(ssu);
+    nw = sqrt(ssw);
+    if (nu > 0.0 && nw > 0.0)
+        rate = (float)((double)trust * nw / (nu + (double)wd * nw + (double)eps));
+    for (i = 0; i < n; ++i) {
+        float g = u[i];
+        if (wd != 0.0f)
+            g = fmaf(wd, w[i], u[i]);
+        /* the decay is already in g: the plain rule on the scaled gradient */
+        update_rule(rate * g, &w[i], &v[i], lr, mu, 0.0f, nesterov);
+    }
+    return rate;
+}
+
 void eager_oracle_sgd(int64_t n, const float *u, float *w, float *v, float lr, float mu,
                       int nthreads)
 {

@@ -74,6 +74,11 @@ def _load():
         lib.eager_oracle_sgd_ex.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int, ctypes.c_int]
+        lib.eager_oracle_sgd_lars.restype = ctypes.c_float
+        lib.eager_oracle_sgd_lars.argtypes = [
+            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int, ctypes.c_float,
+            ctypes.c_float]
         lib.eager_oracle_sgd.restype = None
         lib.eager_oracle_sgd.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -202,6 +207,21 @@ def sgd_f32(u: np.ndarray, w: np.ndarray, v: np.ndarray, lr: float, mu: float,
         assert x.dtype == np.float32 and x.shape == u.shape and x.flags.c_contiguous
     _load().eager_oracle_sgd_ex(u.shape[0], u.ctypes.data, w.ctypes.data, v.ctypes.data,
                                 lr, mu, wd, int(nesterov), nthreads)
+
+
+def sgd_lars_f32(u: np.ndarray, w: np.ndarray, v: np.ndarray, offset: Sequence[int],
+                 numel: Sequence[int], lr: float, mu: float, trust: float, eps: float = 0.0,
+                 wd: float = 0.0, nesterov: bool = False) -> List[float]:
+    """The update rule with a layer-wise rate (layer = bucket), in place on w and v; padding
+    between buckets is not touched.  Returns the rate of every bucket."""
+    for x in (u, w, v):
+        assert x.dtype == np.float32 and x.shape == u.shape and x.flags.c_contiguous
+    lib, rates = _load(), []
+    for lo, n in zip(offset, numel):
+        rates.append(float(lib.eager_oracle_sgd_lars(
+            n, u[lo:].ctypes.data, w[lo:].ctypes.data, v[lo:].ctypes.data, lr, mu, wd,
+            int(nesterov), trust, eps)))
+    return rates
 
 
 # --------------------------------------------------------------------------- fp64 (numpy)

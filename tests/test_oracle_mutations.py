@@ -40,6 +40,16 @@ MUTATIONS = {
         ("g = fmaf(wd, *w, u);", "g = fmaf(wd, u, *w);"),
     "stashed gradient overwrites a pending one":
         ("R[i] = has_stale ? R[i] + g : g;", "R[i] = g;"),
+    "layer-wise rate inverted":
+        ("(double)trust * nw / (nu + (double)wd * nw + (double)eps)",
+         "(double)trust * nu / (nw + (double)wd * nu + (double)eps)"),
+    "layer-wise rate without the weight-decay term":
+        ("(nu + (double)wd * nw + (double)eps)", "(nu + (double)eps)"),
+    "layer-wise rate from squared norms":
+        ("nu = sqrt(ssu);", "nu = ssu;"),
+    "layer-wise rate scales the learning rate instead of the gradient":
+        ("update_rule(rate * g, &w[i], &v[i], lr, mu, 0.0f, nesterov);",
+         "update_rule(g, &w[i], &v[i], rate * lr, mu, 0.0f, nesterov);"),
     "absent process contributes nothing":
         ("""                if (has_stale)
                     s = s + R[p][i];
@@ -63,6 +73,8 @@ def _pins():
     yield pins.test_bf16_widening_matches_torch
     yield pins.test_nonfinite_gradients_propagate
     yield lambda: pins.test_brute_force_with_absent_processes_and_stashes(2, 3)
+    yield pins.test_layerwise_rate_closed_forms
+    yield pins.test_layerwise_rate_properties_and_torch
 
 
 @pytest.mark.parametrize("name", list(MUTATIONS))

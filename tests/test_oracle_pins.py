@@ -355,6 +355,77 @@ def test_update_rule_variants_against_torch_sgd(wd, nesterov):
     assert np.array_equal(w2, w3) and np.array_equal(v2, v3)
 
 
+def test_layerwise_rate_closed_forms():
+    """The layer-wise rate (You, Gitman, Ginsburg 2017) on vectors whose norms are known:
+    w = c everywhere, u = d everywhere, so ||w|| / ||u|| = |c| / |d| whatever n.  Power-of-two
+    values keep every fp32 operation exact."""
+    n = 64
+    for c, d, wd, trust in [(0.5, 0.25, 0.0, 0.5), (2.0, -0.5, 0.25, 1.0), (-1.0, 4.0, 0.0, 0.125)]:
+        u = np.full(n, d, dtype=np.float32)
+        w, v = np.full(n, c, dtype=np.float32), np.zeros(n, dtype=np.float32)
+        (rate,) = eo.sgd_lars_f32(u, w, v, [0], [n], lr=0.5, mu=0.5, trust=trust, wd=wd)
+        want = trust * abs(c) / (abs(d) + wd * abs(c))
+        assert rate == np.float32(want)
+        g = want * (d + wd * c)
+        assert np.all(v == np.float32(g)) and np.all(w == np.float32(c - 0.5 * g))
+    # a layer at zero (fresh biases) or a zero update: rate 1, the plain rule bit for bit
+    rng = np.random.default_rng(3)
+    for u, w0 in [(rng.standard_normal(n).astype(np.float32), np.zeros(n, np.float32)),
+                  (np.zeros(n, np.float32), rng.standard_normal(n).astype(np.float32))]:
+        w, v, w1, v1 = w0.copy(), np.ones(n, np.float32), w0.copy(), np.ones(n, np.float32)
+        assert eo.sgd_lars_f32(u, w, v, [0], [n], 0.1, 0.9, trust=0.001, wd=0.01) == [1.0]
+        eo.sgd_f32(u, w1, v1, 0.1, 0.9, wd=0.01)
+        assert np.array_equal(w, w1) and np.array_equal(v, v1)
+
+
+def test_layerwise_rate_properties_and_torch():
+    """What defines the rule: (1) without weight decay the step does not depend on the scale
+    of the gradient - u and 1024 u give the same new weights (powers of two: exactly);
+    (2) the scaled gradient has norm trust * ||w||; (3) every bucket gets its own rate and
+    the padding between buckets is left alone; (4) over several steps it equals torch's SGD
+    (library routine, momentum and Nesterov) fed with gradients scaled by rates computed
+    with torch.linalg.norm in fp64."""
+    import torch
+    rng = np.random.default_rng(11)
+    offset, numel = [0, 40, 48, 120], [37, 5, 70, 9]
+    arena = 132
+    u = (1e-3 * rng.standard_normal(arena)).astype(np.float32)
+    w0 = (0.02 * rng.standard_normal(arena)).astype(np.float32)
+    v0 = (1e-3 * rng.standard_normal(arena)).astype(np.float32)
+    wa, va, wb, vb = w0.copy(), v0.copy(), w0.copy(), v0.copy()
+    ra = eo.sgd_lars_f32(u, wa, va, offset, numel, 0.1, 0.9, trust=0.01)
+    rb = eo.sgd_lars_f32(u * np.float32(1024), wb, vb, offset, numel, 0.1, 0.9, trust=0.01)
+    assert np.array_equal(wa, wb) and np.array_equal(va, vb)
+    assert [np.float32(x / 1024) for x in ra] == [np.float32(x) for x in rb]
+    assert len(set(ra)) == len(ra)
+    inside = np.zeros(arena, bool)
+    for (lo, n), rate in zip(zip(offset, numel), ra):
+        inside[lo:lo + n] = True
+        scaled = rate * u[lo:lo + n].astype(np.float64)
+        assert np.isclose(np.linalg.norm(scaled), 0.01 * np.linalg.norm(w0[lo:lo + n].astype(np.float64)),
+                          rtol=1e-6)
+        assert np.allclose(va[lo:lo + n], 0.9 * v0[lo:lo + n].astype(np.float64) + scaled, rtol=1e-5, atol=1e-9)
+    assert np.array_equal(wa[~inside], w0[~inside]) and np.array_equal(va[~inside], v0[~inside])
+
+    for wd, nesterov in [(0.0, False), (5e-4, True)]:
+        params = [torch.tensor(w0[lo:lo + n].copy(), requires_grad=True) for lo, n in zip(offset, numel)]
+        opt = torch.optim.SGD(params, lr=0.1, momentum=0.9, nesterov=nesterov)
+        w, v = w0.copy(), np.zeros(arena, np.float32)
+        for t in range(5):
+            ut = (1e-3 * rng.standard_normal(arena)).astype(np.float32)
+            eo.sgd_lars_f32(ut, w, v, offset, numel, 0.1, 0.9, trust=0.02, eps=1e-9, wd=wd,
+                            nesterov=nesterov)
+            for prm, lo, n in zip(params, offset, numel):
+                g = torch.tensor(ut[lo:lo + n]).double()
+                pw = prm.detach().double()
+                nw, ng = torch.linalg.norm(pw), torch.linalg.norm(g)
+                rate = 0.02 * nw / (ng + wd * nw + 1e-9)
+                prm.grad = (rate * (g + wd * pw)).float()
+            opt.step()
+            for prm, lo, n in zip(params, offset, numel):
+                assert np.allclose(w[lo:lo + n], prm.detach().numpy(), rtol=1e-5, atol=1e-8), (wd, t)
+
+
 def test_divides_by_P_not_by_contributors():
     """Algorithm 2 line 6 scales by 1/P whatever the number of active processes.  With
     fresh = 1 and null = 0 the delivered value times P is the number of active
