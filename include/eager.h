@@ -233,7 +233,8 @@ typedef struct {
     double   sumsq_update;
     double   sumsq_params;
     uint64_t nonfinite;
-    uint64_t reserved;
+    float    rate;          /* written by eager_sgd_step_lars; 0 after a round */
+    uint32_t reserved;
 } eager_bucket_stats;
 
 /*
@@ -255,6 +256,31 @@ typedef struct {
 int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes);
 int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspace,
                        int64_t workspace_bytes, void *stream);
+
+/*
+ * eager_sgd_step with a rate per layer (layer = bucket): layer-wise adaptive rate scaling (You,
+ * Gitman, Ginsburg 2017), one more instance of the generic update rule U of Algorithm 2
+ * line 7, for the large batches that the paper's Section 7.3 says need tuned rates.  With
+ * u = update (the averaged result of a round run with recv and without opt), per bucket b over
+ * its finite elements, norms from fp64 sums of squares:
+ *     rate_b = trust * |w_b| / (|u_b| + weight_decay * |w_b| + eps)   if |w_b| > 0 and |u_b| > 0
+ *            = 1                                                      otherwise
+ * (fp64, rounded to fp32 once), then per element, with weight_decay and nesterov as set by
+ * eager_set_update_rule:
+ *     g = rate_b * (u + weight_decay * w);  v' = mu * v + g;
+ *     w' = w - lr * (nesterov ? g + mu * v' : v')
+ * Two passes over the buckets (norms, then update: 8 + 20 bytes per element); padding between
+ * buckets takes the rate of the bucket before it.
+ * Needs eager_stats_attach: the workspace holds the partial sums, and stats[b] of every bucket
+ * in [b0, b1) is overwritten with sumsq_update, sumsq_params (before the step), nonfinite and
+ * rate.  The sums are formed in a fixed order (reproducible run to run); another summation
+ * order can move a rate by one unit in the last place, so against another implementation
+ * compare w and v with a tolerance even in fixed-order mode.
+ * Errors: EINVAL (NULL or misaligned pointers, trust <= 0, eps < 0, non-finite), ESHAPE,
+ * ESTATE (no statistics attached), EDEVICE.  Enqueues on `stream`, never synchronises.
+ */
+int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+                        float trust, float eps, void *stream);
 
 /* Send-buffer validity of one bucket (bit p: R_p holds an undelivered gradient);
  * together with w, v, R and the round index this is all the state a resume needs. */

@@ -25,7 +25,8 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_views",
+    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
+    "eager_sgd_step_views",
     "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
@@ -86,6 +87,8 @@ def _load() -> ctypes.CDLL:
         ctypes.POINTER(Opt), vp]
     lib.eager_stash.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
+    lib.eager_sgd_step_lars.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), ctypes.c_float,
+                                        ctypes.c_float, vp]
     lib.eager_sgd_step_views.argtypes = [vp, i32, i32, vp, i32, ctypes.POINTER(vp),
                                          ctypes.POINTER(vp), ctypes.c_float, ctypes.c_float, vp]
     lib.eager_average_views.argtypes = [vp, i32, i32, i32, ctypes.POINTER(vp), vp]
@@ -246,6 +249,14 @@ class Context:
         self._check(lib.eager_sgd_step(self._h, b0, b1, _ptr(update), ctypes.byref(o),
                                        _stream(stream)), "eager_sgd_step")
 
+    def eager_sgd_step_lars(self, update, opt, trust: float, eps: float = 0.0, b0: int = 0,
+                            b1: Optional[int] = None, stream=None) -> None:
+        b1 = self.n_buckets if b1 is None else b1
+        params, momentum, lr, mu = opt
+        o = Opt(_ptr(params), _ptr(momentum), lr, mu)
+        self._check(lib.eager_sgd_step_lars(self._h, b0, b1, _ptr(update), ctypes.byref(o), trust,
+                                            eps, _stream(stream)), "eager_sgd_step_lars")
+
     def eager_sgd_step_views(self, update, params, momentum, lr: float, mu: float, b0: int = 0,
                              b1: Optional[int] = None, stream=None) -> None:
         b1 = self.n_buckets if b1 is None else b1
@@ -278,7 +289,7 @@ class Context:
 
     def eager_stats_attach(self, stats, workspace, workspace_bytes: int = 0, stream=None) -> None:
         """stats: device buffer of n_buckets x 32 bytes (sumsq_update f64, sumsq_params f64,
-        nonfinite u64, reserved u64), or None to detach; workspace: device buffer."""
+        nonfinite u64, rate f32, reserved u32), or None to detach; workspace: device buffer."""
         self._check(lib.eager_stats_attach(self._h, _ptr(stats), _ptr(workspace), workspace_bytes,
                                            _stream(stream)), "eager_stats_attach")
 

@@ -457,6 +457,56 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const ea
     return EAGER_OK;
 }
 
+int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+                        float trust, float eps, void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (!update || !opt) return fail(ctx, EAGER_EINVAL, "update and opt must not be NULL");
+    if (!aligned16(update)) return fail(ctx, EAGER_EINVAL, "update must be 16-byte aligned");
+    if (!(trust > 0.0f) || std::isinf(trust) || !(eps >= 0.0f) || std::isinf(eps))
+        return fail(ctx, EAGER_EINVAL, "trust must be finite and > 0, eps finite and >= 0");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    if (int st = check_opt(ctx, opt)) return st;
+    if (!ctx->stats)
+        return fail(ctx, EAGER_ESTATE, "the layer-wise rate needs eager_stats_attach (norms and rates "
+                                       "are written to the attached array)");
+    eager::SgdArgs a;
+    a.u = update;
+    a.w = opt->params;
+    a.v = opt->momentum;
+    a.e0 = ctx->offset[b0];
+    a.n = ctx->offset[b1 - 1] + ctx->numel[b1 - 1] - ctx->offset[b0];
+    a.neg_lr = -opt->lr;
+    a.mu = opt->mu;
+    a.wd = ctx->weight_decay;
+    a.nesterov = ctx->nesterov;
+    eager::StatsArgs st;
+    std::memset(&st, 0, sizeof st);
+    st.table = reinterpret_cast<const long long *>(ctx->workspace);
+    st.stats = ctx->stats;
+    st.records = reinterpret_cast<eager::StatsRecord *>(
+        ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
+    st.lane_records = st.records + max_records(ctx);
+    st.n_buckets = ctx->n_buckets;
+    st.e0 = a.e0;
+    st.b_lo = b0;
+    st.b_hi = b1;
+    st.n_records = eager::norms_records(a.n);
+    st.tail_count = static_cast<int>(a.n % 4);
+    st.want_rate = 1;
+    st.trust = trust;
+    st.wd = ctx->weight_decay;
+    st.eps = eps;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t he = eager::launch_norms(a, st, s);
+    if (he == hipSuccess) he = eager::launch_stats_finish(st, s);
+    if (he == hipSuccess) he = eager::launch_sgd_lars(a, st, ctx->fast, s);
+    if (he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "layer-wise update launch failed: %s", hipGetErrorString(he));
+    ctx->err.clear();
+    return EAGER_OK;
+}
+
 namespace {
 int fill_views(eager_ctx *ctx, eager::ViewsArgs &a, int b0, int b1, int n_views,
                float *const *params, float *const *momentum)

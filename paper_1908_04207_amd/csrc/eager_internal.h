@@ -16,7 +16,8 @@ struct BucketStats {
     double sumsq_update;
     double sumsq_params;
     unsigned long long nonfinite;
-    unsigned long long reserved;
+    float rate;
+    unsigned reserved;
 };
 
 // What one wavefront of the round kernel leaves for the finishing kernel: the sums over its
@@ -41,6 +42,10 @@ struct StatsArgs {
     long long n_records;         // wavefronts the round kernel was launched with
     int b_lo, b_hi;              // buckets of the run
     int n_buckets;
+    // layer-wise rate, written next to the totals when want_rate is set:
+    // trust * |w| / (|u| + wd * |w| + eps), or 1 where a norm is zero
+    int want_rate;
+    float trust, wd, eps;
 };
 
 // Everything one launch of the round kernel needs, passed by value in the kernel
@@ -170,6 +175,11 @@ hipError_t launch_stash(const StashArgs &a, bool bf16, hipStream_t stream);
 hipError_t launch_views_sgd(const ViewsArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
 hipError_t launch_views_average(const ViewsArgs &a, const Launch &cfg, hipStream_t stream);
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream);
+// norms of update and parameters per bucket (records for launch_stats_finish), then the update
+// rule with the rate of each element's bucket read from st.stats
+hipError_t launch_norms(const SgdArgs &a, const StatsArgs &st, hipStream_t stream);
+hipError_t launch_sgd_lars(const SgdArgs &a, const StatsArgs &st, bool fast, hipStream_t stream);
+long long norms_records(long long n);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);
 

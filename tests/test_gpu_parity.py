@@ -189,6 +189,81 @@ def test_bucket_statistics(eb, k, clip, dtype):
     assert float(stats.max()) == -1.0
 
 
+@pytest.mark.parametrize("k,clip,order,wd,nesterov", [
+    (2, 3000, 0, 0.0, False), (2, 3000, 1, 5e-4, True), (3, 70001, 0, 5e-4, False),
+    (4, 2500, 0, 0.0, True)])
+def test_layerwise_rate_update(eb, k, clip, order, wd, nesterov):
+    """eager_sgd_step_lars (norms kernel, finishing kernel with the rate, update kernel)
+    against the oracle's layer-wise rule on the result of an unfused round: sums of squares
+    to 1e-10, every rate to one unit in the last place, w and v to 1e-6 normwise - and bit
+    for bit in fixed-order mode whenever all rates agree bitwise (the two sides sum the
+    squares in different orders, which can move a rate by an ulp).  A bucket of zero
+    parameters takes rate 1; a range call leaves the other buckets alone."""
+    from oracle import eager_oracle as eo
+    cfg = shapes.scaled(shapes.config(k), clip)
+    bt = cfg.buckets
+    nb = bt.n_buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, "f32", order, cfg.lr, cfg.mu,
+                seed=51, wd=wd, nesterov=nesterov)
+    with pytest.raises(eb.EagerError) as err:
+        pair.ctx.eager_sgd_step_lars(pair.recv, (pair.w, pair.v, cfg.lr, cfg.mu), 0.01)
+    assert err.value.status == eb.ESTATE
+    stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+    ws_bytes = pair.ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    pair.ctx.eager_stats_attach(stats, ws, ws_bytes)
+    for bad in (0.0, -1.0, float("inf")):
+        with pytest.raises(eb.EagerError):
+            pair.ctx.eager_sgd_step_lars(pair.recv, (pair.w, pair.v, cfg.lr, cfg.mu), bad)
+    # one layer starts at zero (as biases do)
+    zb = nb // 2
+    lo, n = bt.offset[zb], bt.numel[zb]
+    pair.w[lo:lo + n] = 0.0
+    pair.oracle.w[lo:lo + n] = 0.0
+    trust, eps = 0.02, 1e-9
+    bitwise_rounds = 0
+    # in fast mode the update itself differs from the oracle's by rounding, and so do its norms
+    sum_tol, rate_tol = (1e-10, 1.2e-7) if order == 0 else (1e-5, 1e-6)
+    for t in range(6):
+        plan = plan_for(eb, cfg, t)
+        pair.round(plan, pair.fresh_grads(t), fused=False)
+        b0, b1 = (0, nb) if t != 4 else (nb // 3, max(nb // 3 + 1, 2 * nb // 3))
+        w_before = pair.oracle.w.copy()
+        gw_before, gv_before = pair.w.cpu().numpy(), pair.v.cpu().numpy()
+        if t == 4:
+            stats.zero_()
+        pair.ctx.eager_sgd_step_lars(pair.recv, (pair.w, pair.v, cfg.lr, cfg.mu), trust, eps, b0, b1)
+        want_rates = eo.sgd_lars_f32(pair.oracle_recv, pair.oracle.w, pair.oracle.v,
+                                     bt.offset[b0:b1], bt.numel[b0:b1], cfg.lr, cfg.mu, trust, eps,
+                                     wd, nesterov)
+        torch.cuda.synchronize()
+        raw = stats.cpu().numpy().view(np.uint8).reshape(-1, 32)
+        got_rates = raw[:, 24:28].copy().view(np.float32)[:, 0]
+        sums = _read_stats(stats)
+        want_sums = eo.bucket_stats(pair.oracle_recv, w_before, bt.offset, bt.numel)
+        for b in range(b0, b1):
+            for j in (0, 1):
+                assert abs(sums[b][j] - want_sums[b][j]) <= sum_tol * max(want_sums[b][j], 1e-300), (t, b, j)
+            assert sums[b][2] == 0
+            assert abs(float(got_rates[b]) - want_rates[b - b0]) <= rate_tol * want_rates[b - b0], \
+                (t, b, got_rates[b], want_rates[b - b0])
+        if t == 4:
+            assert not raw[:b0].any() and not raw[b1:].any()
+        if t == 0:
+            assert got_rates[zb] == 1.0 and want_rates[zb] == 1.0
+        same = all(np.float32(want_rates[b - b0]) == got_rates[b] for b in range(b0, b1))
+        bitwise = order == 0 and same
+        bitwise_rounds += bitwise
+        pair.compare(exact=bitwise, tol=1e-6, what=f"layer-wise rate t={t} [{b0},{b1})")
+        # outside the range nothing moved
+        w, v = pair.w.cpu().numpy(), pair.v.cpu().numpy()
+        for b in list(range(b0)) + list(range(b1, nb)):
+            sl = slice(bt.offset[b], bt.offset[b] + bt.numel[b])
+            assert np.array_equal(w[sl], gw_before[sl]) and np.array_equal(v[sl], gv_before[sl])
+    if order == 0:
+        assert bitwise_rounds >= 4     # a one-ulp difference of a rate is rare
+
+
 def test_bucket_statistics_are_reproducible(eb):
     """No atomics, fixed trees: two runs of the same rounds give the same bits."""
     cfg = shapes.scaled(shapes.config(2), 5000)
