@@ -148,3 +148,49 @@ def test_full_size_bucket_statistics(eb, k):
             assert abs(got[b, 1] - ssw) <= 1e-9 * max(ssw, 1e-300), (t, b, got[b, 1], ssw)
             assert got[b, 2].view(np.uint64) == 0
     ctx.close()
+
+
+@pytest.mark.parametrize("k", [3, 4])
+def test_full_size_layerwise_rate(eb, k):
+    """eager_sgd_step_lars on whole models (8 buckets of up to 16.8 M elements; 73 buckets of up
+    to 51 M, 355 M elements in all) against the oracle run on the whole arrays: every rate to
+    one unit in the last place, w and v to 1e-6 normwise per bucket, and bit for bit in the
+    buckets whose rate agrees bitwise."""
+    cfg = shapes.config(k)
+    bt = cfg.buckets
+    dev = torch.device("cuda:0")
+    n = bt.arena_numel
+    ctx = eb.Context(cfg.P, bt.offset, bt.numel, eb.F32, eb.ORDER_FIXED)
+    ctx.eager_set_update_rule(5e-4, True)
+    w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
+    v = torch.zeros(n, device=dev)
+    u = torch.empty(n, device=dev)
+    stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
+    nbytes = ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ctx.eager_stats_attach(stats, ws, nbytes)
+    ow, ov = w.cpu().numpy(), v.cpu().numpy()
+    exact = [True] * bt.n_buckets
+    for t in range(2):
+        print(f"{cfg.name} layer-wise rate step {t}", flush=True)
+        wg.fill(u, cfg.seed, t, 0, cfg.grad_sigma)
+        ou = u.cpu().numpy()                      # generator output, not a result of the library
+        ctx.eager_sgd_step_lars(u, (w, v, cfg.lr, cfg.mu), 0.02, 1e-9)
+        want = eo.sgd_lars_f32(ou, ow, ov, bt.offset, bt.numel, cfg.lr, cfg.mu, 0.02, 1e-9,
+                               wd=5e-4, nesterov=True)
+        torch.cuda.synchronize()
+        got = stats.cpu().numpy().view(np.uint8).reshape(-1, 32)[:, 24:28].copy().view(np.float32)[:, 0]
+        gw, gv = w.cpu().numpy(), v.cpu().numpy()
+        for b, (o, m) in enumerate(zip(bt.offset, bt.numel)):
+            assert abs(float(got[b]) - want[b]) <= 1.2e-7 * want[b], (t, b, got[b], want[b])
+            sl = slice(o, o + m)
+            # bitwise only while the bucket's rates have agreed so far: a one-ulp difference
+            # stays in its w and v from then on
+            exact[b] = exact[b] and got[b] == np.float32(want[b])
+            if exact[b]:
+                assert np.array_equal(bits(gw[sl]), bits(ow[sl])), (t, b)
+                assert np.array_equal(bits(gv[sl]), bits(ov[sl])), (t, b)
+            else:
+                assert normwise(gw[sl], ow[sl]) <= 1e-6 and normwise(gv[sl], ov[sl]) <= 1e-6, (t, b)
+    assert sum(exact) >= bt.n_buckets // 2
+    ctx.close()
