@@ -65,7 +65,7 @@ class Workload:
     generator (outside any timed region)."""
 
     def __init__(self, k: int, order: str, launch: dict | None = None, stagger: int = 0,
-                 clip: int = 0, stats: bool = False, unfused: bool = False):
+                 clip: int = 0, stats: bool = False, unfused: bool = False, lars: float = 0.0):
         import torch
         from paper_1908_04207_amd import binding as eb
         from workloads import grads as wg
@@ -95,6 +95,11 @@ class Workload:
             self.R[p].zero_()
         self.w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
         self.v = torch.zeros(n, device=dev)
+        self.lars = lars
+        if lars > 0.0:  # layer-wise rate: needs the receive buffer and the statistics workspace
+            if not stats:   # ... but not the rounds' own by-products: the step forms its norms
+                self.ctx.eager_set_launch("round_stats", 0)
+            stats = unfused = True
         if stats:      # optional per-bucket by-products (norms), computed in the same pass
             nbytes = self.ctx.eager_stats_workspace_bytes()
             self.stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
@@ -134,7 +139,12 @@ class Workload:
         if self.unfused:
             self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=self.recv, opt=None,
                                              stream=self.stream)
-            self.ctx.eager_sgd_step(self.recv, (self.w, self.v, cfg.lr, cfg.mu), stream=self.stream)
+            if self.lars > 0.0:
+                self.ctx.eager_sgd_step_lars(self.recv, (self.w, self.v, cfg.lr, cfg.mu), self.lars,
+                                             1e-9, stream=self.stream)
+            else:
+                self.ctx.eager_sgd_step(self.recv, (self.w, self.v, cfg.lr, cfg.mu),
+                                        stream=self.stream)
         else:
             self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=None,
                                              opt=(self.w, self.v, cfg.lr, cfg.mu),
@@ -147,13 +157,13 @@ class Workload:
 
 
 def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0, clip=0,
-            stats=False, unfused=False):
+            stats=False, unfused=False, lars=0.0):
     """W untimed steps, then K timed steps.  Returns the workload, the wall-clock seconds
     of the K steps (synchronised on both sides), their algorithmic bytes, and the GPU time
     of the same K steps between two HIP events recorded on the launch stream (torch's
     current stream, which is the one the binding launches on)."""
     import torch
-    wl = Workload(k, order, launch, stagger, clip, stats, unfused)
+    wl = Workload(k, order, launch, stagger, clip, stats, unfused, lars)
     wl.prepare(0, warmup + steps)
     for _ in range(warmup):
         wl.step()
@@ -293,6 +303,10 @@ def main() -> int:
                          "algorithmic bytes in the numerator, 8 B/element more traffic)")
     ap.add_argument("--stats", action="store_true",
                     help="also compute the per-bucket norms in every round (eager_stats_attach)")
+    ap.add_argument("--lars", type=float, default=0.0, metavar="TRUST",
+                    help="update rule with a layer-wise rate per bucket (eager_sgd_step_lars with this "
+                         "trust coefficient) on the receive buffer of an unfused round; the numerator "
+                         "stays the fused path's algorithmic bytes")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (P simulated processes share its HBM); "
@@ -304,7 +318,7 @@ def main() -> int:
         return 2
     launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
     wl, wall, nbytes, kern_s = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger,
-                                       a.clip, a.stats, a.unfused)
+                                       a.clip, a.stats, a.unfused, a.lars)
     cfg = wl.cfg
     total_b = sum(nbytes)
     traffic = MEASURED_TRAFFIC.get(cfg.name)
@@ -321,7 +335,8 @@ def main() -> int:
         "config": {"workload": cfg.name, "P": cfg.P, "mode": cfg.mode, "grad_dtype": cfg.grad_dtype,
                    "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
                    "order": a.order, "launch": launch, "stagger": a.stagger,
-                   "bucket_stats": a.stats, "unfused": a.unfused},
+                   "bucket_stats": a.stats or a.lars > 0, "unfused": a.unfused or a.lars > 0,
+                   "lars_trust": a.lars},
         "steps_per_s": round(a.steps / wall, 2),
         "pct_hbm_peak": round(100.0 * total_b / wall / 1e9 / HBM_PEAK_GBS, 2),
         "alg_bytes_per_step": round(total_b / a.steps),

@@ -309,6 +309,9 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
  *                round: threads per workgroup (64 default, 128, 256), groups of 4 elements
  *                per thread (1 default, 2, 4), resident workgroups per CU (-1 = no cap,
  *                default; 1..32)
+ *   "round_stats" 1 (default) = with statistics attached every round writes the by-products;
+ *                0 = rounds leave them alone (for callers that attach the statistics only as
+ *                the workspace of eager_sgd_step_lars, which forms its own norms)
  *   "block"      threads per workgroup: 64 (default), 128 or 256
  *   "blocks_per_cu" 0 = chosen from the round (default); -1 = no cap; 1..32 = at most
  *                that many workgroups resident per CU

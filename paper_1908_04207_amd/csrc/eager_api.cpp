@@ -165,7 +165,8 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
     a.mu = opt ? opt->mu : 0.0f;
     a.wd = ctx->weight_decay;
     a.nesterov = ctx->nesterov;
-    if (ctx->stats) {
+    const bool round_stats = ctx->stats && ctx->launch.round_stats;
+    if (round_stats) {
         if (ctx->launch.compact == 0 || (ctx->launch.chunk != 0 && ctx->launch.chunk != 16))
             return fail(ctx, EAGER_ESTATE, "bucket statistics need compact = 1 and chunk = 16");
         a.stats.table = reinterpret_cast<const long long *>(ctx->workspace);
@@ -194,7 +195,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
         a.gload = split ? plan->mask : (plan->mask | late);
         a.store = split ? 0 : late;
-        if (ctx->stats) {
+        if (round_stats) {
             a.stats.e0 = a.e0;
             a.stats.b_lo = b;
             a.stats.b_hi = e;
@@ -205,7 +206,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
                                             static_cast<hipStream_t>(stream));
         if (he != hipSuccess)
             return fail(ctx, EAGER_EDEVICE, "round kernel launch failed: %s", hipGetErrorString(he));
-        if (ctx->stats) {
+        if (round_stats) {
             he = eager::launch_stats_finish(a.stats, static_cast<hipStream_t>(stream));
             if (he != hipSuccess)
                 return fail(ctx, EAGER_EDEVICE, "statistics kernel launch failed: %s",
@@ -692,6 +693,9 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
         if (value < -1 || value == 0 || value > 32)
             return fail(ctx, EAGER_EINVAL, "carry_blocks_per_cu must be -1 or 1..32");
         ctx->launch.carry_blocks_per_cu = value;
+    } else if (!std::strcmp(key, "round_stats")) {
+        if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "round_stats must be 0 or 1");
+        ctx->launch.round_stats = value;
     } else {
         return fail(ctx, EAGER_EINVAL, "unknown launch key '%s'", key);
     }

@@ -162,6 +162,7 @@ struct Launch {
     int xcd_map = 0;       // slot kernel: 1 = contiguous eighth of the run per XCD
     int carry_block = 64;  // carry kernel: threads per workgroup
     int carry_vec = 1;     // carry kernel: lane-vectors per thread and iteration (1, 2, 4)
+    int round_stats = 1;           // 0: rounds skip the by-products although statistics are attached
     int carry_blocks_per_cu = -1;  // carry kernel: -1 no cap, else max workgroups per CU
 };
 

@@ -224,9 +224,14 @@ def test_layerwise_rate_update(eb, k, clip, order, wd, nesterov):
     bitwise_rounds = 0
     # in fast mode the update itself differs from the oracle's by rounding, and so do its norms
     sum_tol, rate_tol = (1e-10, 1.2e-7) if order == 0 else (1e-5, 1e-6)
+    if k == 4:      # statistics attached only as this call's workspace: rounds leave them alone
+        pair.ctx.eager_set_launch("round_stats", 0)
     for t in range(6):
         plan = plan_for(eb, cfg, t)
+        stats.fill_(-1.0)
         pair.round(plan, pair.fresh_grads(t), fused=False)
+        torch.cuda.synchronize()
+        assert (float(stats.max()) == -1.0) == (k == 4)
         b0, b1 = (0, nb) if t != 4 else (nb // 3, max(nb // 3 + 1, 2 * nb // 3))
         w_before = pair.oracle.w.copy()
         gw_before, gv_before = pair.w.cpu().numpy(), pair.v.cpu().numpy()
