@@ -1190,10 +1190,24 @@ constexpr long long kMaxGridThreads = 1ll << 31;
 // Parameters and momentum above this size are streamed past the caches (see slot_vectors).
 constexpr long long kStateCacheBytes = 256ll << 20;
 
-// Resident wavefronts per CU of the weight-view kernels when the caller leaves it open
-// (measured, 8 views of 2^26 elements: update 6.36 TB/s with 3, 5.68 uncapped; average 6.50
-// with 4, 5.82 uncapped).
-constexpr int kViewsSgdWaves = 3, kViewsAverageWaves = 4;
+// Resident wavefronts per CU of the weight-view kernels when the caller leaves it open: what
+// counts is the KiB of loads in flight per CU, about 38 for the update (1 + 2 per view loads
+// per lane, views in chunks of 8) and 32 for the average (one load per view, chunks of 16).
+// Measured optima, update: 12, 8, 4, 3, 2 wavefronts for 1, 2, 4, 8, 16 views (6.8, 6.6, 6.5,
+// 6.4, 6.2 TB/s; uncapped 6.7, 6.2, 5.8, 5.7, 5.5); average: uncapped, 16, 8, 4, 4 (6.8, 6.8,
+// 6.7, 6.5, 6.3 TB/s; uncapped 6.8, 6.5, 6.0, 5.8, 5.7).
+int views_sgd_waves(int n_views)
+{
+    const int loads = 1 + 2 * (n_views < 8 ? n_views : 8);
+    const int w = (38 + loads / 2) / loads;
+    return w < 2 ? 2 : w;
+}
+int views_average_waves(int n_views)
+{
+    const int loads = n_views < 16 ? n_views : 16;
+    const int w = 32 / loads;
+    return w > 16 ? -1 : w < 4 ? 4 : w;
+}
 
 // Resident workgroups per CU when the caller leaves the choice to the library: measured
 // optima of the rank-chunk kernel with 64-thread workgroups for 1, 2 and 4 chunks of 8.
@@ -1512,13 +1526,14 @@ hipError_t launch_views(K kernel, const ViewsArgs &a, const Launch &cfg, int aut
 
 hipError_t launch_views_sgd(const ViewsArgs &a, bool fast, const Launch &cfg, hipStream_t stream)
 {
-    return fast ? launch_views(views_sgd_kernel<true>, a, cfg, kViewsSgdWaves, stream)
-                : launch_views(views_sgd_kernel<false>, a, cfg, kViewsSgdWaves, stream);
+    const int waves = views_sgd_waves(a.n_views);
+    return fast ? launch_views(views_sgd_kernel<true>, a, cfg, waves, stream)
+                : launch_views(views_sgd_kernel<false>, a, cfg, waves, stream);
 }
 
 hipError_t launch_views_average(const ViewsArgs &a, const Launch &cfg, hipStream_t stream)
 {
-    return launch_views(views_average_kernel, a, cfg, kViewsAverageWaves, stream);
+    return launch_views(views_average_kernel, a, cfg, views_average_waves(a.n_views), stream);
 }
 
 hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_t stream)
