@@ -585,6 +585,79 @@ def test_round_captured_in_a_graph(eb):
         _ = (pair.w * 2).sum().item()                  # unrelated eager work and a sync
 
 
+def test_update_rules_and_views_captured_in_a_graph(eb):
+    """The other entry points a training loop strings together - an unfused round, the update
+    rule with a layer-wise rate (three kernels, partial sums in the caller's workspace), the
+    update of several weight views and their average - captured as ONE graph and replayed on
+    new gradients with eager work and synchronisations in between.  Every replay must leave
+    exactly the bits that the same calls leave when made eagerly on a second copy of the
+    state (the eager calls are the ones the other tests hold against the oracle)."""
+    cfg = shapes.scaled(shapes.config(2), 4000)
+    bt = cfg.buckets
+    nb, P, n = bt.n_buckets, cfg.P, bt.arena_numel
+    dev = torch.device("cuda:0")
+    full = (1 << P) - 1
+
+    class Side:
+        def __init__(self):
+            self.ctx = eb.Context(P, bt.offset, bt.numel, eb.F32, eb.ORDER_FIXED)
+            self.ctx.eager_set_update_rule(5e-4, True)
+            self.G = [torch.zeros(n, device=dev) for _ in range(P)]
+            self.R = [torch.zeros(n, device=dev) for _ in range(P)]
+            self.recv = torch.zeros(n, device=dev)
+            self.w = [wg.fill(torch.empty(n, device=dev), 7, 0, wg.PARAM_RANK + i, 0.02) for i in range(4)]
+            self.v = [torch.zeros(n, device=dev) for _ in range(4)]
+            self.stats = torch.zeros(nb * 4, dtype=torch.float64, device=dev)
+            nbytes = self.ctx.eager_stats_workspace_bytes()
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            self.ctx.eager_stats_attach(self.stats, self.ws, nbytes)
+            self.ctx.eager_set_launch("round_stats", 0)
+
+        def calls(self, step, stream=None):
+            self.ctx.eager_partial_allreduce(eb.make_plan(eb.QUORUM, P, step, full), self.G, self.R,
+                                             recv=self.recv, stream=stream)
+            self.ctx.eager_sgd_step_lars(self.recv, (self.w[0], self.v[0], 0.1, 0.9), 0.02, 1e-9,
+                                         stream=stream)
+            self.ctx.eager_sgd_step_views(self.recv, self.w[1:], self.v[1:], 0.1, 0.9, stream=stream)
+            self.ctx.eager_average_views(self.w[1:], stream=stream)
+
+        def load(self, t):
+            for p in range(P):
+                wg.fill(self.G[p], 7, t, p, 1e-3)
+
+    eager, replayed = Side(), Side()
+    for side in (eager, replayed):                     # warm-up: loads every kernel
+        side.load(0)
+        side.calls(0)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        graph.capture_begin()
+        replayed.calls(1, stream=stream)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(stream)
+    for t in range(1, 5):
+        eager.load(t)
+        replayed.load(t)
+        eager.calls(t)
+        graph.replay()
+        torch.cuda.synchronize()
+        for i in range(4):
+            assert torch.equal(eager.w[i], replayed.w[i]) and torch.equal(eager.v[i], replayed.v[i]), (t, i)
+        assert torch.equal(eager.recv, replayed.recv)
+        assert torch.equal(eager.stats.view(torch.int64), replayed.stats.view(torch.int64))
+        assert not torch.equal(eager.w[0], eager.w[1])
+        _ = (eager.w[0] * 2).sum().item()              # unrelated eager work and a sync
+    # the host state of the replayed side was advanced by the capture only (round 1); the
+    # replays touched no host state, so the library still refuses a second round 1
+    with pytest.raises(eb.EagerError):
+        replayed.calls(1)
+    eager.ctx.close()
+    replayed.ctx.close()
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_nothing_is_written_outside_the_buffers(eb, dtype):
     """All arenas carved out of one allocation with guard zones between them; after rounds in
