@@ -243,7 +243,7 @@ typedef struct {
  *   stats      device array of n_buckets entries, 16-byte aligned, caller-owned; NULL detaches
  *   workspace  device memory, 16-byte aligned, caller-owned, at least
  *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table, one
- *              32-byte record per wavefront of the round kernel and a few per bucket there.  It must stay
+ *              32-byte record per wavefront of the round kernel and 129 per bucket there.  It must stay
  *              allocated while attached, and is shared by all calls of this context: with
  *              statistics attached, the calls of a context must be ordered (one stream, or
  *              events), and no other context may use the same workspace concurrently

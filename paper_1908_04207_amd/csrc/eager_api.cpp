@@ -4,6 +4,7 @@
 #include "../../include/eager.h"
 #include "eager_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -66,6 +67,29 @@ int64_t max_records(const eager_ctx *ctx)
 {
     const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
     return span / 256 + 8;
+}
+
+// Fills the parts of the statistics arguments that do not depend on the run: where the bucket
+// table, the records, the lane records and the partials live in the caller's workspace.
+void stats_layout(const eager_ctx *ctx, eager::StatsArgs &st)
+{
+    st.table = reinterpret_cast<const long long *>(ctx->workspace);
+    st.stats = ctx->stats;
+    st.records = reinterpret_cast<eager::StatsRecord *>(
+        ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
+    st.lane_records = st.records + max_records(ctx);
+    st.partials = st.lane_records + (static_cast<int64_t>(ctx->n_buckets) + 1) * 64;
+    st.n_buckets = ctx->n_buckets;
+}
+
+// Workgroups that add up the records of one bucket before the finishing kernel: from the
+// largest bucket of the run (one record per 256 elements)
+int stats_slices(const eager_ctx *ctx, int b0, int b1)
+{
+    int64_t most = 0;
+    for (int b = b0; b < b1; ++b) most = std::max(most, ctx->numel[b] / 256);
+    const int64_t s = (most + eager::kStatsRecordsPerSlice - 1) / eager::kStatsRecordsPerSlice;
+    return static_cast<int>(std::min<int64_t>(std::max<int64_t>(s, 1), eager::kStatsMaxSlices));
 }
 
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
@@ -169,12 +193,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
     if (round_stats) {
         if (ctx->launch.compact == 0 || (ctx->launch.chunk != 0 && ctx->launch.chunk != 16))
             return fail(ctx, EAGER_ESTATE, "bucket statistics need compact = 1 and chunk = 16");
-        a.stats.table = reinterpret_cast<const long long *>(ctx->workspace);
-        a.stats.stats = ctx->stats;
-        a.stats.records = reinterpret_cast<eager::StatsRecord *>(
-            ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
-        a.stats.lane_records = a.stats.records + max_records(ctx);
-        a.stats.n_buckets = ctx->n_buckets;
+        stats_layout(ctx, a.stats);
     }
 
     // Consecutive buckets whose send buffers are in the same state form one run = one
@@ -201,6 +220,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
             a.stats.b_hi = e;
             a.stats.n_records = eager::slot_records(a.n, ctx->bf16, ctx->launch.block);
             a.stats.tail_count = eager::slot_tail(a.n, ctx->bf16);
+            a.stats.slices = stats_slices(ctx, b, e);
         }
         hipError_t he = eager::launch_round(a, ctx->bf16, ctx->fast, ctx->launch,
                                             static_cast<hipStream_t>(stream));
@@ -483,12 +503,8 @@ int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, con
     a.nesterov = ctx->nesterov;
     eager::StatsArgs st;
     std::memset(&st, 0, sizeof st);
-    st.table = reinterpret_cast<const long long *>(ctx->workspace);
-    st.stats = ctx->stats;
-    st.records = reinterpret_cast<eager::StatsRecord *>(
-        ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
-    st.lane_records = st.records + max_records(ctx);
-    st.n_buckets = ctx->n_buckets;
+    stats_layout(ctx, st);
+    st.slices = stats_slices(ctx, b0, b1);
     st.e0 = a.e0;
     st.b_lo = b0;
     st.b_hi = b1;
@@ -589,9 +605,11 @@ int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask)
 int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes)
 {
     if (!ctx || !bytes) return EAGER_EINVAL;
-    // bucket table, one record per wavefront, (n_buckets + 1) blocks of 64 lane records
+    // bucket table, one record per wavefront, (n_buckets + 1) blocks of 64 lane records, one
+    // block of partials per bucket
     *bytes = static_cast<int64_t>(ctx->n_buckets) * 16 +
-             (max_records(ctx) + (static_cast<int64_t>(ctx->n_buckets) + 1) * 64) *
+             (max_records(ctx) + (static_cast<int64_t>(ctx->n_buckets) + 1) * 64 +
+              static_cast<int64_t>(ctx->n_buckets) * eager::kStatsMaxSlices) *
                  static_cast<int64_t>(sizeof(eager::StatsRecord));
     return EAGER_OK;
 }

@@ -46,7 +46,13 @@ struct StatsArgs {
     // trust * |w| / (|u| + wd * |w| + eps), or 1 where a norm is zero
     int want_rate;
     float trust, wd, eps;
+    // A bucket with many records is added up by `slices` workgroups first, one partial each
+    // (partials[bucket * kStatsMaxSlices + slice]); 1: the finishing kernel reads the records.
+    StatsRecord *partials;
+    int slices;
 };
+constexpr int kStatsMaxSlices = 64;
+constexpr long long kStatsRecordsPerSlice = 4096;
 
 // Everything one launch of the round kernel needs, passed by value in the kernel
 // argument segment: the P gradient and send-buffer bases stay in scalar registers and

@@ -721,29 +721,19 @@ __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
         slot_scalar<BF16, STATS>(a, a.e0 + nvec * 4 + threadIdx.x);
 }
 
-// One workgroup per bucket of the run: adds the records of the wavefronts whose 256 elements
-// touch the bucket (they are consecutive) - a uniform wavefront's sums, or a mixed wavefront's
-// lane records of this bucket - and the records of the ragged tail; wavefront sums by DPP, the
-// 4 wavefronts of the workgroup through LDS; one thread writes the bucket's totals.
-__global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
+// Adds the plain records (one per wavefront whose elements all lie in one bucket) with index in
+// [lo, hi) that belong to bucket b: 8 independent loads per thread in flight, wavefront sums by
+// DPP, the 4 wavefronts of the workgroup through LDS.  The totals arrive in thread 0.
+__device__ __forceinline__ void add_records(const StatsRecord *records, long long lo, long long hi,
+                                            int b, double &su, double &sw, double &nf)
 {
-    __shared__ double part_u[4], part_w[4];
-    __shared__ unsigned part_n[4];
-    const int b = a.b_lo + static_cast<int>(blockIdx.x);
-    const long long start = a.table[2 * b], end = a.table[2 * b + 1];
-    long long w0 = (start - a.e0) / 256, w1 = (end - a.e0 + 255) / 256;
-    if (w1 > a.n_records) w1 = a.n_records;
-    double su = 0.0, sw = 0.0;
-    unsigned nf = 0u;
-    // a large bucket has thousands of records for the one workgroup: 8 independent loads per
-    // thread are in flight together
     constexpr int K = 8;
-    for (long long wb = w0 + threadIdx.x; wb < w1; wb += static_cast<long long>(blockDim.x) * K) {
+    for (long long wb = lo + threadIdx.x; wb < hi; wb += static_cast<long long>(blockDim.x) * K) {
         StatsRecord r[K];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
             const long long w = wb + static_cast<long long>(k) * blockDim.x;
-            if (w < w1) r[k] = a.records[w];
+            if (w < hi) r[k] = records[w];
             else r[k].bucket = -2;
         }
 #pragma unroll
@@ -754,6 +744,77 @@ __global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
                 nf += r[k].nf;
             }
         }
+    }
+}
+
+// (the count travels as a double: integers below 2^53 add exactly, and a 32-bit sum could
+// overflow on a bucket of billions of elements)
+__device__ __forceinline__ void workgroup_sum(double &su, double &sw, double &nf)
+{
+    __shared__ double part_u[4], part_w[4], part_n[4];
+    su = wave_sum(su);
+    sw = wave_sum(sw);
+    nf = wave_sum(nf);
+    const unsigned wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63u) == 0u) {
+        part_u[wave] = su;
+        part_w[wave] = sw;
+        part_n[wave] = nf;
+    }
+    __syncthreads();
+    su = (part_u[0] + part_u[1]) + (part_u[2] + part_u[3]);
+    sw = (part_w[0] + part_w[1]) + (part_w[2] + part_w[3]);
+    nf = (part_n[0] + part_n[1]) + (part_n[2] + part_n[3]);
+}
+
+// records of bucket b: [w0, w1)
+__device__ __forceinline__ void bucket_records(const StatsArgs &a, int b, long long &w0, long long &w1)
+{
+    const long long start = a.table[2 * b], end = a.table[2 * b + 1];
+    w0 = (start - a.e0) / 256;
+    w1 = (end - a.e0 + 255) / 256;
+    if (w1 > a.n_records) w1 = a.n_records;
+}
+
+// First stage for buckets with many records (a flat model is ONE bucket: millions of records):
+// workgroup (bucket, slice) adds one slice of the bucket's plain records and leaves a partial.
+__global__ __launch_bounds__(256) void stats_slice_kernel(const StatsArgs a)
+{
+    const int b = a.b_lo + static_cast<int>(blockIdx.x);
+    const int s = static_cast<int>(blockIdx.y);
+    long long w0, w1;
+    bucket_records(a, b, w0, w1);
+    const long long len = (w1 - w0 + a.slices - 1) / a.slices;
+    const long long lo = w0 + s * len, hi = lo + len < w1 ? lo + len : w1;
+    double su = 0.0, sw = 0.0, nf = 0.0;
+    add_records(a.records, lo, hi, b, su, sw, nf);
+    workgroup_sum(su, sw, nf);
+    if (threadIdx.x == 0) {
+        // a slice holds at most 2^33 / 256 / slices records of 256 elements: the count fits
+        const StatsRecord out = {su, sw, b, static_cast<unsigned>(nf), 0};
+        a.partials[static_cast<long long>(b) * kStatsMaxSlices + s] = out;
+    }
+}
+
+// One workgroup per bucket of the run: adds the records of the wavefronts whose 256 elements
+// touch the bucket (they are consecutive) - a uniform wavefront's sums (or the partials of the
+// first stage), a mixed wavefront's lane records of this bucket - and the records of the ragged
+// tail; one thread writes the bucket's totals.
+__global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
+{
+    const int b = a.b_lo + static_cast<int>(blockIdx.x);
+    long long w0, w1;
+    bucket_records(a, b, w0, w1);
+    double su = 0.0, sw = 0.0, nf = 0.0;
+    if (a.slices > 1) {
+        if (static_cast<int>(threadIdx.x) < a.slices) {
+            const StatsRecord r = a.partials[static_cast<long long>(b) * kStatsMaxSlices + threadIdx.x];
+            su = r.ssu;
+            sw = r.ssw;
+            nf = r.nf;
+        }
+    } else {
+        add_records(a.records, w0, w1, b, su, sw, nf);
     }
     // Only the first and the last wavefront of the bucket can be mixed: wavefront 0 of this
     // workgroup takes the lane records of the first, wavefront 1 those of the last, one lane
@@ -778,21 +839,12 @@ __global__ __launch_bounds__(256) void stats_finish_kernel(const StatsArgs a)
             nf += tr.nf;
         }
     }
-    su = wave_sum(su);
-    sw = wave_sum(sw);
-    nf = wave_sum(nf);
-    const unsigned wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63u) == 0u) {
-        part_u[wave] = su;
-        part_w[wave] = sw;
-        part_n[wave] = nf;
-    }
-    __syncthreads();
+    workgroup_sum(su, sw, nf);
     if (threadIdx.x == 0) {
         BucketStats out;
-        out.sumsq_update = (part_u[0] + part_u[1]) + (part_u[2] + part_u[3]);
-        out.sumsq_params = (part_w[0] + part_w[1]) + (part_w[2] + part_w[3]);
-        out.nonfinite = static_cast<unsigned long long>(part_n[0]) + part_n[1] + part_n[2] + part_n[3];
+        out.sumsq_update = su;
+        out.sumsq_params = sw;
+        out.nonfinite = static_cast<unsigned long long>(nf);
         out.rate = 0.0f;
         if (a.want_rate) {
             // fp64 square roots and division, one rounding to fp32 at the end
@@ -1492,6 +1544,11 @@ hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream)
 {
     const int n = a.b_hi - a.b_lo;
     if (n <= 0) return hipSuccess;
+    if (a.slices > kStatsMaxSlices || a.slices < 1) return hipErrorInvalidValue;
+    if (a.slices > 1) {
+        hipLaunchKernelGGL(stats_slice_kernel, dim3(n, a.slices), dim3(256), 0, stream, a);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(stats_finish_kernel, dim3(n), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
