@@ -205,3 +205,54 @@ def test_allreduce_validation_happens_before_any_launch():
     c.eager_set_valid(1, 0b1010)
     assert c.eager_get_valid(1) == 0b1010 and c.eager_get_valid(0) == 0
     c.close()
+
+
+def test_other_entry_points_validate_on_the_host():
+    """Stash, rounds with absent processes, weight views, the layer-wise rule, statistics and
+    launch keys: every bad call is refused before anything is launched (fake addresses)."""
+    P = 4
+    c = eb.Context(P, [0, 8], [8, 8])
+    fake = [0x10000 + 0x1000 * p for p in range(P)]
+    opt = (0x90000, 0xA0000, 0.1, 0.9)
+
+    def refused(status, fn):
+        with pytest.raises(eb.EagerError) as e:
+            fn()
+        assert e.value.status == status, str(e.value)
+
+    refused(eb.EINVAL, lambda: c.eager_stash(P, 0x10000, 0x20000, stream=0))         # no such process
+    refused(eb.EINVAL, lambda: c.eager_stash(-1, 0x10000, 0x20000, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_stash(0, 0, 0x20000, stream=0))               # NULL
+    refused(eb.EINVAL, lambda: c.eager_stash(0, 0x10000, 0x20004, stream=0))         # misaligned
+    refused(eb.EINVAL, lambda: c.eager_stash(0, 0x10000, 0x20000, 1, 1, stream=0))   # empty range
+    plan = eb.make_plan(eb.SOLO, P, 0, 0b0011)
+    refused(eb.ESTATE, lambda: c.eager_partial_allreduce_lagging(plan, 0b0001, fake, fake, opt=opt,
+                                                                 stream=0))          # absent and active
+    refused(eb.ESTATE, lambda: c.eager_partial_allreduce_lagging(plan, 0b10000, fake, fake, opt=opt,
+                                                                 stream=0))          # beyond P
+    refused(eb.EINVAL, lambda: c.eager_partial_allreduce_lagging(plan, 0b0100, [fake[0], fake[1], None, None],
+                                                                 fake, opt=opt, stream=0))  # late, no gradient
+    views = [0x100000, 0x200000, 0x300000]
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_views(0x90000, [], [], 0.1, 0.9, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_views(0x90000, [0x100000] * 65, [0x200000] * 65, 0.1, 0.9,
+                                                      stream=0))
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_views(0x90000, [views[0], views[0]], views[1:], 0.1, 0.9,
+                                                      stream=0))                     # one buffer twice
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_views(0x90004, views[:1], views[1:2], 0.1, 0.9, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_average_views([views[0], 0], stream=0))
+    refused(eb.EINVAL, lambda: c.eager_average_views([views[0], views[0]], stream=0))
+    refused(eb.ESTATE, lambda: c.eager_sgd_step_lars(0x90000, opt, 0.01, stream=0))  # nothing attached
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_lars(0x90000, opt, 0.0, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_lars(0x90000, opt, 0.01, -1.0, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_sgd_step_lars(0, opt, 0.01, stream=0))
+    need = c.eager_stats_workspace_bytes()
+    assert need >= 2 * 16 + 32 * (8 + 3 * 64)          # table, records, lane records at least
+    refused(eb.EINVAL, lambda: c.eager_stats_attach(0x400000, 0x500000, need - 1, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_stats_attach(0x400008, 0x500000, need, stream=0))
+    refused(eb.EINVAL, lambda: c.eager_stats_attach(0x400000, 0, need, stream=0))
+    c.eager_stats_attach(None, None, stream=0)         # detaching what is not attached is fine
+    for key, bad in (("round_stats", 2), ("split", 3), ("nt_state", 2), ("xcd_map", -1), ("chunk", 5),
+                     ("blocks_per_cu", 33), ("carry_vec", 3), ("compact", 2)):
+        refused(eb.EINVAL, lambda: c.eager_set_launch(key, bad))
+    refused(eb.EINVAL, lambda: c.eager_set_update_rule(float("nan"), False))
+    c.close()
