@@ -256,3 +256,21 @@ def test_other_entry_points_validate_on_the_host():
         refused(eb.EINVAL, lambda: c.eager_set_launch(key, bad))
     refused(eb.EINVAL, lambda: c.eager_set_update_rule(float("nan"), False))
     c.close()
+
+
+def test_host_side_under_address_and_ub_sanitizers(tmp_path):
+    """eager_api.cpp compiled without the kernels (the launchers and the two runtime calls it
+    uses are recorders in tests/c/api_host_sanitized.cpp) and driven on the CPU under
+    AddressSanitizer and UndefinedBehaviorSanitizer: how a bucket range is cut into launches,
+    the fused and the split form, absent processes, stash runs, views, statistics and the
+    layer-wise rule, state after every call, error paths, a 2^31-element bucket."""
+    import subprocess
+    exe = tmp_path / "api_host_sanitized"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-static-libasan", "-Wall", "-Wextra", "-Werror",
+                           "-D__HIP_PLATFORM_AMD__", "-isystem", "/opt/rocm/include",
+                           os.path.join(ROOT, "tests", "c", "api_host_sanitized.cpp"),
+                           os.path.join(ROOT, "paper_1908_04207_amd", "csrc", "eager_api.cpp"),
+                           "-o", str(exe)])
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.stdout[-500:], r.stderr[-2000:])
