@@ -23,7 +23,12 @@
 //   * round_kernel: the earlier form (fixed chunks of ranks, stand-in loads for absent
 //     streams), kept for comparison;
 //   * optional per-bucket norms as by-products: DPP sums inside wavefronts, LDS across
-//     them (stats_*).
+//     them (stats_*); norms_kernel + lars_kernel use them for an update rule with a rate
+//     per bucket;
+//   * around the round, for processes that lag by more than one round: stash_kernel (a late
+//     gradient into a send buffer), views_sgd_kernel / views_average_kernel (a weight view
+//     per process: update of several views from one read of the result, model average);
+//   * sgd_kernel: the update rule alone on a receive buffer (the unfused path).
 #include "eager_internal.h"
 
 #include <mutex>
