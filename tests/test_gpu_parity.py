@@ -755,3 +755,23 @@ def test_calibration_kernels(eb):
     eb.eager_calib_read(a, a.numel() * 4, sink)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
+
+
+def test_library_from_plain_c_without_python_buffers(eb, tmp_path):
+    """tests/c/abi_gpu_roundtrip.c: hipMalloc'ed buffers, rounds of every mode, a stash and the
+    unfused path through the C ABI from a C program (gcc, C99), compared with the C oracle by
+    memcmp.  No torch, no binding: the boundary is usable as the plain C library it claims to be."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.dirname(eb.LIB_PATH)
+    exe = tmp_path / "abi_gpu_roundtrip"
+    subprocess.check_call(["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-ffp-contract=off",
+                           "-D__HIP_PLATFORM_AMD__", "-isystem", "/opt/rocm/include",
+                           "-I", os.path.join(root, "include"),
+                           os.path.join(root, "tests", "c", "abi_gpu_roundtrip.c"),
+                           os.path.join(root, "oracle", "eager_oracle.c"), "-o", str(exe),
+                           "-L", lib_dir, "-leager", "-L/opt/rocm/lib", "-lamdhip64", "-lm", "-fopenmp",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"])
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout[-500:], r.stderr[-1500:])
