@@ -274,3 +274,15 @@ def test_host_side_under_address_and_ub_sanitizers(tmp_path):
                            "-o", str(exe)])
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.strip() == "ok", (r.stdout[-500:], r.stderr[-2000:])
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built HIP library the binding refuses to load: there is no CPU path."""
+    monkeypatch.setattr(eb, "LIB_PATH", str(tmp_path / "libeager.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        eb._load()
+    import inspect
+    from paper_1908_04207_amd import async_sgd, hyperplane, streams_bench
+    for mod in (eb, async_sgd, hyperplane, streams_bench):
+        src = inspect.getsource(mod)
+        assert "import oracle" not in src and "from oracle" not in src, mod.__name__
