@@ -355,6 +355,7 @@ def main() -> int:
         c = copy_ceiling_gbs()
         out["measured_ceiling_GBs"] = {"copy_read_plus_write": round(c["copy"], 1),
                                        "read_only": round(c["read"], 1)}
+        out["pct_of_measured_copy"] = round(100.0 * achieved / c["copy"], 1)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
