@@ -194,3 +194,69 @@ def test_full_size_layerwise_rate(eb, k):
                 assert normwise(gw[sl], ow[sl]) <= 1e-6 and normwise(gv[sl], ov[sl]) <= 1e-6, (t, b)
     assert sum(exact) >= bt.n_buckets // 2
     ctx.close()
+
+
+def test_arena_of_more_than_2_to_32_elements(eb):
+    """64-bit indexing end to end: P = 2, two buckets of 2^32 + 4099 and 1021 elements (17 GB per
+    array, 120 GB in all), a fused round with a late process, a stash, an unfused round with
+    eager_sgd_step; sampled elements - both ends of the buckets, around 2^31 and 2^32, around
+    tile boundaries, random positions - against the oracle, bit for bit."""
+    P = 2
+    big = (1 << 32) + 4099
+    offset, numel = [0, (big + 3) // 4 * 4], [big, 1021]
+    n = offset[1] + numel[1]
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(5)
+    picks = [np.arange(12), big - 1 - np.arange(12), offset[1] + np.arange(12),
+             offset[1] + numel[1] - 1 - np.arange(12), rng.integers(0, big, 20000)]
+    for centre in ((1 << 31), (1 << 32), (1 << 32) - (1 << 20)):
+        picks.append(centre + np.arange(-300, 300))
+    S = np.unique(np.concatenate(picks)).astype(np.int64)
+    S = S[(S < big) | ((S >= offset[1]) & (S < n))]
+    S_t = torch.from_numpy(S)
+    S_dev = S_t.to(dev)
+    seed, lr, mu = 777, 0.1, 0.9
+
+    ctx = eb.Context(P, offset, numel, eb.F32, eb.ORDER_FIXED)
+    G = [torch.empty(n, device=dev) for _ in range(P)]
+    R = [torch.empty(n, device=dev) for _ in range(P)]
+    w = wg.fill(torch.empty(n, device=dev), seed, 0, wg.PARAM_RANK, 0.02)
+    v = torch.zeros(n, device=dev)
+    recv = torch.empty(n, device=dev)
+    oracle = eo.OracleState(P, [0], [len(S)], len(S), wg.values_at(S_t, seed, 0, wg.PARAM_RANK, 0.02).numpy(),
+                            lr, mu)
+    orecv = np.zeros(len(S), dtype=np.float32)
+
+    def check(what):
+        torch.cuda.synchronize()
+        valid = ctx.eager_get_valid(0)
+        assert valid == ctx.eager_get_valid(1) == oracle.valid[0], what
+        assert np.array_equal(bits(w[S_dev].cpu().numpy()), bits(oracle.w)), what
+        assert np.array_equal(bits(v[S_dev].cpu().numpy()), bits(oracle.v)), what
+        for p in range(P):
+            if (valid >> p) & 1:
+                assert np.array_equal(bits(R[p][S_dev].cpu().numpy()), bits(oracle.R[p])), (what, p)
+
+    for t, mask in enumerate((0b01, 0b10, 0b11)):
+        print(f"2^32 elements, round {t}", flush=True)
+        for p in range(P):
+            wg.fill(G[p], seed, t, p, 1e-3)
+        Gs = [as_oracle_grad(wg.grad_at(S_t, seed, t, p, 1e-3, torch.float32)) for p in range(P)]
+        plan = eb.make_plan(eb.SOLO, P, t, mask)
+        if t == 1:          # unfused: receive buffer, then the update rule alone
+            ctx.eager_partial_allreduce(plan, G, R, recv=recv)
+            ctx.eager_sgd_step(recv, (w, v, lr, mu))
+            oracle.round(mask, Gs, recv=orecv, fused=False)
+            oracle.sgd(orecv)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(recv[S_dev].cpu().numpy()), bits(orecv))
+        else:
+            ctx.eager_partial_allreduce(plan, G, R, opt=(w, v, lr, mu))
+            oracle.round(mask, Gs)
+        check(f"round {t}")
+        if t == 0:          # process 1 was late; it finishes another gradient before the next round
+            wg.fill(G[1], seed, 100, 1, 1e-3)
+            ctx.eager_stash(1, G[1], R[1])
+            oracle.stash(1, as_oracle_grad(wg.grad_at(S_t, seed, 100, 1, 1e-3, torch.float32)))
+            check("stash")
+    ctx.close()
