@@ -775,3 +775,86 @@ def test_library_from_plain_c_without_python_buffers(eb, tmp_path):
                            "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"])
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), (r.stdout[-500:], r.stderr[-1500:])
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_seeded_random_cases_bitwise(eb, seed):
+    """Everything drawn from a seed: P, gradient type, the bucket table (empty buckets, sizes
+    that are not multiples of the vector, one large bucket), the launch form, the update-rule
+    variant, and per round the participation set, who is absent, which bucket range is
+    stepped, fused or unfused, an occasional stash and an occasional hand-set send-buffer
+    state.  Fixed-order mode: bit for bit against the oracle after every call."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "bf16" if rng.integers(0, 3) == 0 else "f32"
+    align = 8 if dtype == "bf16" else 4
+    P = int(rng.choice([1, 2, 3, 4, 7, 8, 15, 16, 17, 31, 32, 33, 48, 64]))
+    nb = int(rng.integers(1, 9))
+    numel = [int(rng.choice([0, 1, 3, 5, 64, 255, 257, 1000, 4097])) for _ in range(nb)]
+    numel[int(rng.integers(0, nb))] = int(rng.integers(20000, 60000))
+    off, cur = [], int(rng.integers(0, 3)) * align          # the first bucket need not start at 0
+    for m in numel:
+        off.append(cur)
+        cur = (cur + m + align - 1) // align * align + int(rng.integers(0, 2)) * align
+    arena = max(off[-1] + numel[-1], align)
+    wd = float(rng.choice([0.0, 0.0, 1e-3]))
+    nesterov = bool(rng.integers(0, 2))
+    pair = Pair(eb, P, off, numel, arena, dtype, eb.ORDER_FIXED, lr=0.05, mu=0.8, seed=seed,
+                wd=wd, nesterov=nesterov)
+    launch = {}
+    if rng.integers(0, 2):
+        launch["split"] = int(rng.integers(0, 3))
+    if rng.integers(0, 3) == 0:
+        launch["compact"] = 0
+    else:
+        if rng.integers(0, 2):
+            launch["chunk"] = int(rng.choice([8, 16]))
+        if rng.integers(0, 2):
+            launch["block"] = int(rng.choice([64, 128, 256]))
+        if rng.integers(0, 2):
+            launch["xcd_map"] = 1
+    if rng.integers(0, 2):
+        launch["blocks_per_cu"] = int(rng.choice([-1, 1, 3, 8]))
+    if rng.integers(0, 2):
+        launch["nt_state"] = int(rng.integers(0, 2))
+    for key, val in launch.items():
+        pair.ctx.eager_set_launch(key, val)
+    full = (1 << P) - 1
+    what = f"seed {seed} P={P} {dtype} numel={numel} launch={launch}"
+    for t in range(6):
+        mask = int(rng.integers(1, full + 1)) if P < 63 else int(rng.integers(1, 1 << 62)) | 1
+        if rng.integers(0, 4) == 0:
+            mask = full
+        rest = full & ~mask
+        absent = rest & int(rng.integers(0, 1 << min(P, 62))) if rng.integers(0, 2) else 0
+        b0 = int(rng.integers(0, nb))
+        b1 = int(rng.integers(b0 + 1, nb + 1))
+        if rng.integers(0, 2):
+            b0, b1 = 0, nb
+        fused = bool(rng.integers(0, 4))
+        initiator = [p for p in range(P) if (mask >> p) & 1][0]
+        plan = eb.make_plan(eb.QUORUM, P, t, mask, initiator=initiator)
+        G = pair.fresh_grads(t)
+        pair.round(plan, G, b0, b1, fused=fused, want_recv=bool(rng.integers(0, 2)),
+                   absent=absent if absent else None)
+        if not fused:
+            pair.sgd(b0, b1)
+        pair.compare(exact=True, check_recv=not fused, b0=b0, b1=b1, what=f"{what} round {t}")
+        if rng.integers(0, 3) == 0:
+            p = int(rng.integers(0, P))
+            g = wg.fill(torch.empty(arena, dtype=pair.dtype), seed, 50 + t, p, 1e-3)
+            pair.stash(p, g)
+            pair.compare(exact=True, what=f"{what} stash after round {t}")
+        if rng.integers(0, 5) == 0:
+            # a send-buffer state set by hand (as a resume does); buffers declared non-empty
+            # must hold data on both sides
+            b = int(rng.integers(0, nb))
+            state = int(rng.integers(0, 1 << min(P, 62))) & full
+            lo, hi = off[b], off[b] + numel[b]
+            for p in range(P):
+                if (state >> p) & 1 and not (pair.oracle.valid[b] >> p) & 1:
+                    fill = wg.fill(torch.empty(arena), seed, 90 + t, p, 1e-3)
+                    pair.R[p][lo:hi] = fill[lo:hi].cuda()
+                    pair.oracle.R[p][lo:hi] = fill[lo:hi].numpy()
+            pair.ctx.eager_set_valid(b, state)
+            pair.oracle.valid[b] = state
+    pair.compare(exact=True, what=what + " end")
