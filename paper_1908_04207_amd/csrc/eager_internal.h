@@ -159,8 +159,8 @@ struct Launch {
     int unroll = 1;        // 16-byte vectors per thread and iteration
     int nontemporal = 1;   // streaming hints on G and R
     int chunk = 0;         // ranks whose loads are in flight together; 0: chosen from P
-    int compact = 1;       // fp32 gradients: 1 = compacted stream list (slot kernel), 0 = rank
-                           // chunks with stand-in loads (always used for bf16 gradients)
+    int compact = 1;       // 1 = compacted stream list (slot kernel), 0 = rank chunks with
+                           // stand-in loads (the earlier form, kept for comparison)
     int split = 0;         // 0: chosen from the round; 1: one fused kernel; 2: reduce+update
                            // kernel followed by a carry (copy) kernel
     int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
