@@ -76,7 +76,7 @@ class Workload:
 
     def __init__(self, k: int, order: str, launch: dict | None = None, stagger: int = 0,
                  clip: int = 0, stats: bool = False, unfused: bool = False, lars: float = 0.0,
-                 light_setup: bool = False):
+                 light_setup: bool = False, views: bool = False):
         import torch
         from paper_1908_04207_amd import binding as eb
         from workloads import grads as wg
@@ -124,6 +124,12 @@ class Workload:
             self.stats = torch.zeros(bt.n_buckets * 4, dtype=torch.float64, device=dev)
             self.stats_ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
             self.ctx.eager_stats_attach(self.stats, self.stats_ws, nbytes)
+        self.views = views
+        if views:      # a weight view per process (Section 5, last paragraph): the round goes to
+            unfused = True   # the receive buffer, every process applies it to its own w_p, v_p
+            self.wp = [self.w] + [self.w.clone() for _ in range(cfg.P - 1)]
+            self.vp = [self.v] + [torch.zeros(n, device=dev) for _ in range(cfg.P - 1)]
+            self.wpp, self.vpp = self.ctx.pointers(self.wp), self.ctx.pointers(self.vp)
         self.unfused = unfused
         if unfused:    # A/B: receive buffer first, update rule as a second pass
             self.recv = torch.empty(n, device=dev)
@@ -158,7 +164,10 @@ class Workload:
         if self.unfused:
             self.ctx.eager_partial_allreduce(plan, self.Gp, self.Rp, recv=self.recv, opt=None,
                                              stream=self.stream)
-            if self.lars > 0.0:
+            if self.views:
+                self.ctx.eager_sgd_step_views(self.recv, self.wpp, self.vpp, cfg.lr, cfg.mu,
+                                              stream=self.stream)
+            elif self.lars > 0.0:
                 self.ctx.eager_sgd_step_lars(self.recv, (self.w, self.v, cfg.lr, cfg.mu), self.lars,
                                              1e-9, stream=self.stream)
             else:
@@ -176,13 +185,13 @@ class Workload:
 
 
 def run_gpu(k: int, steps: int, warmup: int, order: str, launch=None, stagger=0, clip=0,
-            stats=False, unfused=False, lars=0.0, light_setup=False):
+            stats=False, unfused=False, lars=0.0, light_setup=False, views=False):
     """W untimed steps, then K timed steps.  Returns the workload, the wall-clock seconds
     of the K steps (synchronised on both sides), their algorithmic bytes, and the GPU time
     of the same K steps between two HIP events recorded on the launch stream (torch's
     current stream, which is the one the binding launches on)."""
     import torch
-    wl = Workload(k, order, launch, stagger, clip, stats, unfused, lars, light_setup)
+    wl = Workload(k, order, launch, stagger, clip, stats, unfused, lars, light_setup, views)
     wl.prepare(0, warmup + steps)
     for _ in range(warmup):
         wl.step()
@@ -322,6 +331,10 @@ def main() -> int:
                          "algorithmic bytes in the numerator, 8 B/element more traffic)")
     ap.add_argument("--stats", action="store_true",
                     help="also compute the per-bucket norms in every round (eager_stats_attach)")
+    ap.add_argument("--views", action="store_true",
+                    help="a weight view per process: the round goes to the receive buffer and "
+                         "eager_sgd_step_views applies it to all P views (P x (w, v) more memory; the "
+                         "numerator stays the single-view path's algorithmic bytes)")
     ap.add_argument("--light-setup", action="store_true",
                     help="inputs with few kernel dispatches (every process's gradient arena is a copy "
                          "of process 0's): for `rocprofv3 --pmc` runs on the largest configurations")
@@ -340,7 +353,7 @@ def main() -> int:
         return 2
     launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
     wl, wall, nbytes, kern_s = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger,
-                                       a.clip, a.stats, a.unfused, a.lars, a.light_setup)
+                                       a.clip, a.stats, a.unfused, a.lars, a.light_setup, a.views)
     cfg = wl.cfg
     total_b = sum(nbytes)
     traffic = MEASURED_TRAFFIC.get(cfg.name)
@@ -358,7 +371,7 @@ def main() -> int:
                    "elements_per_process": cfg.numel, "buckets": cfg.buckets.n_buckets,
                    "order": a.order, "launch": launch, "stagger": a.stagger,
                    "bucket_stats": a.stats or a.lars > 0, "unfused": a.unfused or a.lars > 0,
-                   "lars_trust": a.lars},
+                   "lars_trust": a.lars, "weight_views": cfg.P if a.views else 1},
         "steps_per_s": round(a.steps / wall, 2),
         "pct_hbm_peak": round(100.0 * total_b / wall / 1e9 / HBM_PEAK_GBS, 2),
         "alg_bytes_per_step": round(total_b / a.steps),

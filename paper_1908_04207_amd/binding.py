@@ -260,8 +260,9 @@ class Context:
     def eager_sgd_step_views(self, update, params, momentum, lr: float, mu: float, b0: int = 0,
                              b1: Optional[int] = None, stream=None) -> None:
         b1 = self.n_buckets if b1 is None else b1
+        tab = lambda x: x if isinstance(x, ctypes.Array) else self.pointers(x)  # noqa: E731
         self._check(lib.eager_sgd_step_views(self._h, b0, b1, _ptr(update), len(params),
-                                             self.pointers(params), self.pointers(momentum),
+                                             tab(params), tab(momentum),
                                              lr, mu, _stream(stream)), "eager_sgd_step_views")
 
     def eager_average_views(self, views, b0: int = 0, b1: Optional[int] = None, stream=None) -> None:
