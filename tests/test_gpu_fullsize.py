@@ -56,8 +56,8 @@ def sample_indices(cfg, n_random=30000, seed=0):
 # largest configuration: 15 copies of 1.56e9 elements in one launch, which is where a grid
 # would exceed the device's limit of 2^32 threads if the launcher did not cap it.
 @pytest.mark.parametrize("k,steps,order,launch", [
-    (2, 8, 0, {}), (2, 4, 1, {}), (3, 5, 0, {}), (4, 3, 0, {}), (5, 3, 0, {}), (5, 2, 1, {}),
-    (5, 2, 0, {"split": 2})])
+    (2, 8, 0, {}), (2, 4, 1, {}), (3, 5, 0, {}), (3, 3, 1, {}), (4, 3, 0, {}), (4, 2, 1, {}),
+    (5, 3, 0, {}), (5, 2, 1, {}), (5, 2, 0, {"split": 2}), (4, 2, 0, {"split": 1})])
 def test_full_size_sampled(eb, k, steps, order, launch):
     cfg = shapes.config(k)
     bt = cfg.buckets
