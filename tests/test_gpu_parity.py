@@ -858,3 +858,42 @@ def test_seeded_random_cases_bitwise(eb, seed):
             pair.ctx.eager_set_valid(b, state)
             pair.oracle.valid[b] = state
     pair.compare(exact=True, what=what + " end")
+
+
+def test_bucket_statistics_of_a_bucket_with_many_records(eb):
+    """A bucket of 2.2 M elements between small ones: its 8.6 k wavefront records are added up in
+    slices by the first-stage kernel (more than 4096 records), the small buckets' directly; sums
+    against the oracle's numpy sums, fused round and layer-wise step, a range that starts inside
+    the run."""
+    from oracle import eager_oracle as eo
+    numel = [130, 2_200_003, 77, 40_001]
+    off, cur = [], 0
+    for m in numel:
+        off.append(cur)
+        cur = (cur + m + 3) // 4 * 4
+    pair = Pair(eb, 3, off, numel, cur, "f32", eb.ORDER_FIXED, seed=61)
+    nb = len(numel)
+    stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+    nbytes = pair.ctx.eager_stats_workspace_bytes()
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    pair.ctx.eager_stats_attach(stats, ws, nbytes)
+    for t, (mask, b0, b1) in enumerate([(0b011, 0, nb), (0b101, 1, 3), (0b111, 0, nb)]):
+        w_before = pair.oracle.w.copy()
+        pair.round(eb.make_plan(eb.SOLO, 3, t, mask), pair.fresh_grads(t), b0, b1, want_recv=True)
+        pair.compare(exact=True, check_recv=True, b0=b0, b1=b1, what=f"round {t}")
+        got = _read_stats(stats)
+        want = eo.bucket_stats(pair.oracle_recv, w_before, off, numel)
+        for b in range(b0, b1):
+            for j in (0, 1):
+                assert abs(got[b][j] - want[b][j]) <= 1e-10 * max(want[b][j], 1e-300), (t, b, j)
+            assert got[b][2] == 0
+    pair.round(eb.make_plan(eb.SOLO, 3, 3, 0b110), pair.fresh_grads(3), fused=False)
+    pair.ctx.eager_sgd_step_lars(pair.recv, (pair.w, pair.v, pair.lr, pair.mu), 0.02, 1e-9)
+    rates = eo.sgd_lars_f32(pair.oracle_recv, pair.oracle.w, pair.oracle.v, off, numel, pair.lr,
+                            pair.mu, 0.02, 1e-9)
+    torch.cuda.synchronize()
+    got_rates = stats.cpu().numpy().view(np.uint8).reshape(-1, 32)[:, 24:28].copy().view(np.float32)[:, 0]
+    for b in range(nb):
+        assert abs(float(got_rates[b]) - rates[b]) <= 1.2e-7 * rates[b], (b, got_rates[b], rates[b])
+    pair.compare(exact=all(np.float32(r) == g for r, g in zip(rates, got_rates)), tol=1e-6,
+                 what="layer-wise step")
