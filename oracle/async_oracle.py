@@ -39,9 +39,10 @@ def simulate(P: int, n: int, w0: np.ndarray, lr: float, mu: float, mode: str, ro
              gradient: Callable[[int, int, np.ndarray], np.ndarray],
              quorum: int = 0, seed: int = 0, sync_every: int = 0, keep_results: bool = False):
     """Run until `rounds` executions.  Returns a dict with the final weight and momentum
-    views, send buffers and their validity, per-process counters, the per-round NAP, the
-    gradients of processes still waiting at the open collective ("held") and, on request,
-    every result that was put into the receive buffer."""
+    views, send buffers and their validity, per-process counters, per round the NAP, the set
+    of active processes and the time of execution, the gradients of processes still waiting
+    at the open collective ("held") and, on request, every result that was put into the
+    receive buffer."""
     w = [np.ascontiguousarray(w0, dtype=np.float32).copy() for _ in range(P)]
     v = [np.zeros(n, dtype=np.float32) for _ in range(P)]
     send = [np.zeros(n, dtype=np.float32) for _ in range(P)]
@@ -53,7 +54,8 @@ def simulate(P: int, n: int, w0: np.ndarray, lr: float, mu: float, mode: str, ro
     blocked: List[int] = []
     fresh = {}
     executed = 0
-    log = {"nap": [], "late_calls": [0] * P, "missed": [0] * P, "time_ms": 0.0, "results": []}
+    log = {"nap": [], "late_calls": [0] * P, "missed": [0] * P, "time_ms": 0.0, "results": [],
+           "active": [], "round_time_ms": []}
 
     def read_receive_buffer(p: int) -> None:
         eo.sgd_f32(receive, w[p], v[p], lr, mu)
@@ -105,6 +107,8 @@ def simulate(P: int, n: int, w0: np.ndarray, lr: float, mu: float, mode: str, ro
         has_stale = [False] * P
         executed += 1
         log["nap"].append(len(blocked))
+        log["active"].append(active)
+        log["round_time_ms"].append(t)
         for p in blocked:
             read_receive_buffer(p)
             calls_done[p] += 1

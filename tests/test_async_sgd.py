@@ -101,6 +101,44 @@ def test_missed_results_make_weights_differ_and_synchronisation_repairs_it():
     assert np.allclose(sync["w"][0], np.mean(free["w"], axis=0), atol=1e-6)
 
 
+def _distinct_ms(p, k):
+    """Compute times whose partial sums do not tie (a mixing hash of (p, k): no linear
+    structure that sums could cancel), some of them long."""
+    u = eo.initiator_hash(p * 1000003 + 17, k) / float(1 << 64)
+    return 1.0 + u * (6.0 if (p + k) % 5 == 0 else 1.0)
+
+
+def test_what_triggers_a_round():
+    """Section 4: solo - the first process to reach the open collective triggers it alone
+    (NAP = 1 when no two arrive together); majority - it waits for the designated initiator
+    of the shared seed, who is therefore always among the active; quorum q - exactly q
+    processes are active; quorum P - everybody, every round, nobody is ever late, and the
+    round ends with the slowest process: T_r = T_{r-1} + max_p c_p(r)."""
+    P, n, T = 8, 4, 60
+    g = _int_gradient(n)
+    w0 = np.zeros(n, np.float32)
+    solo = ao.simulate(P, n, w0, 0.1, 0.0, "solo", T, _distinct_ms, g)
+    assert solo["nap"] == [1] * T and all(bin(m).count("1") == 1 for m in solo["active"])
+    assert solo["round_time_ms"] == sorted(solo["round_time_ms"])
+    assert solo["round_time_ms"][0] == min(_distinct_ms(p, 0) for p in range(P))
+    for seed in (1, 2, 3):
+        maj = ao.simulate(P, n, w0, 0.1, 0.0, "majority", T, _distinct_ms, g, seed=seed)
+        for r, mask in enumerate(maj["active"]):
+            assert (mask >> (eo.initiator_hash(seed, r) % P)) & 1, (seed, r)
+        assert 1 <= min(maj["nap"]) and max(maj["nap"]) <= P and len(set(maj["nap"])) > 1
+        assert maj["time_ms"] >= solo["time_ms"]
+    for q in (2, 5):
+        out = ao.simulate(P, n, w0, 0.1, 0.0, "quorum", T, _distinct_ms, g, quorum=q)
+        assert out["nap"] == [q] * T
+    full = ao.simulate(P, n, w0, 0.1, 0.0, "quorum", T, _distinct_ms, g, quorum=P)
+    assert full["nap"] == [P] * T and full["late_calls"] == [0] * P and full["missed"] == [0] * P
+    t = 0.0
+    for r in range(T):
+        t += max(_distinct_ms(p, r) for p in range(P))
+        assert abs(full["round_time_ms"][r] - t) < 1e-9
+    assert full["time_ms"] > maj["time_ms"] > 0
+
+
 # ------------------------------------------------------------------ GPU: library loop == oracle loop
 @pytest.fixture(scope="module")
 def asgd():
