@@ -39,8 +39,8 @@ def simulate(P: int, n: int, w0: np.ndarray, lr: float, mu: float, mode: str, ro
              gradient: Callable[[int, int, np.ndarray], np.ndarray],
              quorum: int = 0, seed: int = 0, sync_every: int = 0, keep_results: bool = False):
     """Run until `rounds` executions.  Returns a dict with the final weight and momentum
-    views, send buffers and their validity, per-process counters, per round the NAP, the set
-    of active processes and the time of execution, the gradients of processes still waiting
+    views, send buffers and their validity, per-process counters (and which results each process applied),
+    per round the NAP, the set of active processes and the time of execution, the gradients of processes still waiting
     at the open collective ("held") and, on request, every result that was put into the
     receive buffer."""
     w = [np.ascontiguousarray(w0, dtype=np.float32).copy() for _ in range(P)]
@@ -55,11 +55,12 @@ def simulate(P: int, n: int, w0: np.ndarray, lr: float, mu: float, mode: str, ro
     fresh = {}
     executed = 0
     log = {"nap": [], "late_calls": [0] * P, "missed": [0] * P, "time_ms": 0.0, "results": [],
-           "active": [], "round_time_ms": []}
+           "active": [], "round_time_ms": [], "applied": [[] for _ in range(P)]}
 
     def read_receive_buffer(p: int) -> None:
         eo.sgd_f32(receive, w[p], v[p], lr, mu)
         log["missed"][p] += (executed - 1) - last_applied[p] - 1
+        log["applied"][p].append(executed - 1)
         last_applied[p] = executed - 1
 
     while executed < rounds:

@@ -80,6 +80,11 @@ def test_every_gradient_is_delivered_exactly_once(mode, kw):
     for p in range(P):
         if out["missed"][p] == 0 and out["late_calls"][p] == 0:
             assert np.array_equal(-out["w"][p].astype(np.float64) * P, delivered)
+        # every process holds exactly the results it read, each once, in order (lr = 1, mu = 0)
+        seen = out["applied"][p]
+        assert seen == sorted(set(seen)) and len(seen) + out["missed"][p] <= T
+        assert np.array_equal(-out["w"][p].astype(np.float64),
+                              sum((out["results"][r].astype(np.float64) for r in seen), np.zeros(n)))
 
 
 def test_missed_results_make_weights_differ_and_synchronisation_repairs_it():
@@ -137,6 +142,49 @@ def test_what_triggers_a_round():
         t += max(_distinct_ms(p, r) for p in range(P))
         assert abs(full["round_time_ms"][r] - t) < 1e-9
     assert full["time_ms"] > maj["time_ms"] > 0
+
+
+ASYNC_MUTATIONS = {
+    "a late gradient overwrites a pending one":
+        ("eo.stash_f32(g, send[p], has_stale[p])", "eo.stash_f32(g, send[p], False)"),
+    "the latest result is applied again":
+        ("if last_applied[p] < executed - 1:", "if executed > 0:"),
+    "majority does not wait for its initiator":
+        ("fire = eo.initiator_hash(seed, executed) % P in blocked", "fire = True"),
+    "quorum waits for one process too many":
+        ("fire = len(blocked) >= quorum", "fire = len(blocked) > quorum"),
+    "processes that are still computing are treated as late":
+        ("absent=everyone & ~active)", "absent=0)"),
+    "send buffers are not emptied by a round":
+        ("        has_stale = [False] * P\n        executed += 1", "        executed += 1"),
+    "an active process does not read the result":
+        ("        for p in blocked:\n            read_receive_buffer(p)\n", "        for p in blocked:\n"),
+}
+
+
+@pytest.mark.parametrize("name", list(ASYNC_MUTATIONS))
+def test_a_planted_mistake_in_the_loop_fails_a_pin(name, monkeypatch):
+    """The pins above bite: each mistake planted in a copy of the oracle's event loop makes
+    one of them fail (on the CPU; the GPU path is not involved)."""
+    import inspect
+    old, new = ASYNC_MUTATIONS[name]
+    src = inspect.getsource(ao.simulate)
+    old, new = old.replace("\\n", "\n"), new.replace("\\n", "\n")
+    assert src.count(old) == 1, f"mutation site not unique: {old!r}"
+    scope = dict(vars(ao))
+    exec(compile(src.replace(old, new), "<mutant>", "exec"), scope)
+    monkeypatch.setattr(ao, "simulate", scope["simulate"])
+    caught = False
+    for pin in (test_equal_compute_times_are_synchronous_sgd, test_what_triggers_a_round,
+                lambda: test_every_gradient_is_delivered_exactly_once("solo", {}),
+                lambda: test_every_gradient_is_delivered_exactly_once("majority", {"seed": 5}),
+                lambda: test_every_gradient_is_delivered_exactly_once("quorum", {"quorum": 2})):
+        try:
+            pin()
+        except (AssertionError, ValueError, IndexError, KeyError):
+            caught = True
+            break
+    assert caught, f"no pin noticed: {name}"
 
 
 # ------------------------------------------------------------------ GPU: library loop == oracle loop
