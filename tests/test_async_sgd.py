@@ -169,7 +169,6 @@ def test_a_planted_mistake_in_the_loop_fails_a_pin(name, monkeypatch):
     import inspect
     old, new = ASYNC_MUTATIONS[name]
     src = inspect.getsource(ao.simulate)
-    old, new = old.replace("\\n", "\n"), new.replace("\\n", "\n")
     assert src.count(old) == 1, f"mutation site not unique: {old!r}"
     scope = dict(vars(ao))
     exec(compile(src.replace(old, new), "<mutant>", "exec"), scope)
