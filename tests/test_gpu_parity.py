@@ -861,12 +861,12 @@ def test_seeded_random_cases_bitwise(eb, seed):
 
 
 def test_bucket_statistics_of_a_bucket_with_many_records(eb):
-    """A bucket of 2.2 M elements between small ones: its 8.6 k wavefront records are added up in
+    """A bucket of 4.4 M elements between small ones: its 17 k wavefront records are added up in
     slices by the first-stage kernel (more than 4096 records), the small buckets' directly; sums
     against the oracle's numpy sums, fused round and layer-wise step, a range that starts inside
     the run."""
     from oracle import eager_oracle as eo
-    numel = [130, 2_200_003, 77, 40_001]
+    numel = [130, 4_400_003, 77, 40_001]
     off, cur = [], 0
     for m in numel:
         off.append(cur)
