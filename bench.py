@@ -351,6 +351,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    from paper_1908_04207_amd import build as hip_build
+    hip_build.ensure_built()             # compiles only if no library has been built
     launch = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in a.launch.split(",") if kv}
     wl, wall, nbytes, kern_s = run_gpu(a.config, a.steps, a.warmup, a.order, launch, a.stagger,
                                        a.clip, a.stats, a.unfused, a.lars, a.light_setup, a.views)

@@ -27,5 +27,11 @@ def build(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """For the test suite, the smoke run and the benchmark: compile only if no library has
+    been built yet (the binding itself never builds: without a library it raises)."""
+    return LIB if os.path.exists(LIB) else build(verbose=True)
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra=sys.argv[1:]))

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only if there is none it is compiled first
+    # (hipcc cross-compiles gfx950 without a GPU)
+    from paper_1908_04207_amd import build
+    build.ensure_built()
 
 
 @pytest.fixture(scope="session", autouse=True)
