@@ -61,7 +61,7 @@ typedef enum {
 #define EAGER_FLAG_STRICT_QUORUM 1u
 
 /* Participation of one round: bit p of `mask` is the response bit s_t^p of Section 6.1
- * ("my update was included").  nap = number of active processes (Section 7.1). */
+ * (whether the process's update entered this round's result).  nap = number of active processes (Section 7.1). */
 typedef struct {
     int32_t  mode;        /* eager_mode */
     int32_t  P;

@@ -16,8 +16,9 @@
  *     gradient and its send buffer becomes empty (G_null).
  *   - Algorithm 2, line 6: the result is the sum of the contributions times 1/P (P, not
  *     the number of contributors); lines 7-8: the update rule U is applied to it.
- *   - Section 6.1: the per-process bit s_t^i "my update was included" is the
- *     participation mask; a rejected update is added in the next round, exactly once.
+ *   - Section 6.1: the per-process bit s_t^i (did this process's update enter the result
+ *     of round t) is the participation mask; a rejected update is added in the next round,
+ *     exactly once.
  *
  * Readings where the paper is silent (they are conventions of this repository):
  *   - U is heavy-ball momentum SGD, v <- mu*v + u, w <- w - lr*v, each as one fused

@@ -23,7 +23,7 @@ rounds executed so far r):
            so its weights drift away from the others'.  Its next call is k + 1.
 
 Every `sync_every` rounds the models are synchronised: every w_p and v_p is replaced by the
-average over the processes ("we periodically synchronize the models across all processes").
+average over the processes (the periodic model synchronisation that Section 5 prescribes).
 
 All arithmetic runs in the library: the round (`eager_partial_allreduce_lagging`, receive
 buffer only), the update rule on the weight views of the processes that see a result
