@@ -1,5 +1,5 @@
 """Hyperplane regression trained with eager-SGD through the library (the paper's one fully
-synthetic experiment: Section 7.2, "Hyperplane Regression, Light Load Imbalance", Fig. 10).
+synthetic experiment: Section 7.2, the hyperplane regression under light load imbalance, Fig. 10).
 
     y = a_0 x_0 + ... + a_{d-1} x_{d-1} + noise,   d = 8192,
     model = one linear layer (d weights + bias = 8,193 parameters, Table 1),
