@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeager.so")
-SOURCES = ["eager_round_kernels.hip", "eager_aux_kernels.hip", "eager_api.cpp"]
+SOURCES = ["eager_round_kernels.hip", "eager_chunk_kernels.hip", "eager_aux_kernels.hip",
+           "eager_api.cpp"]
 
 # -ffp-contract=off: the fixed-order mode defines every rounding; fused multiply-adds are
 # written out where they are meant.  Packed fp32 instructions are switched off.

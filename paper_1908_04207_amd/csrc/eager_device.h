@@ -268,7 +268,7 @@ hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, unsig
     return hipGetLastError();
 }
 
-unsigned grid_for(long long nvec, long long per_block, int max_blocks)
+inline unsigned grid_for(long long nvec, long long per_block, int max_blocks)
 {
     long long g = (nvec + per_block - 1) / per_block;
     if (g < 1) g = 1;

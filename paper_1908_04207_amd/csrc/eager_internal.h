@@ -174,6 +174,9 @@ struct Launch {
 
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
+// the rank-chunk form of the round ("compact" = 0)
+hipError_t launch_round_chunks(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
+                               hipStream_t stream);
 hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream);
 hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
 long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch
