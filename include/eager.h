@@ -100,6 +100,12 @@ int eager_destroy(eager_ctx *ctx);                 /* NULL is allowed */
 const char *eager_last_error(const eager_ctx *ctx);
 const char *eager_status_string(int status);
 
+/* Digest of the sources and headers this library was compiled from, as the build script
+ * computes it ("unknown" for a build that bypassed the script); static storage.  The test
+ * suite compares it with the digest of the sources in the tree, so that a stale library is
+ * never the one that gets tested or timed. */
+const char *eager_source_hash(void);
+
 /*
  * Decide who is active in round `step` from the times (ms, host array of P doubles,
  * measured from a common origin per round) at which the processes reach the collective.

@@ -22,7 +22,7 @@ FLAG_STRICT_QUORUM = 1
 MAX_P = 64
 
 EXPORTS = (
-    "eager_create", "eager_destroy", "eager_last_error", "eager_status_string",
+    "eager_create", "eager_destroy", "eager_last_error", "eager_status_string", "eager_source_hash",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
     "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
@@ -73,6 +73,8 @@ def _load() -> ctypes.CDLL:
     lib.eager_last_error.restype = ctypes.c_char_p
     lib.eager_status_string.argtypes = [i32]
     lib.eager_status_string.restype = ctypes.c_char_p
+    lib.eager_source_hash.argtypes = []
+    lib.eager_source_hash.restype = ctypes.c_char_p
     lib.eager_plan_participation.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), u64, u64,
                                              ctypes.c_double, ctypes.c_uint32,
                                              ctypes.POINTER(Plan)]
@@ -121,6 +123,11 @@ def _stream(stream) -> Optional[int]:
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream
+
+
+def source_hash() -> str:
+    """Digest of the sources the loaded library was built from."""
+    return lib.eager_source_hash().decode()
 
 
 def status_string(status: int) -> str:

@@ -25,7 +25,8 @@ struct eager_ctx {
     eager::Launch launch;
     float weight_decay = 0.0f;         // update rule variants (eager_set_update_rule)
     int nesterov = 0;
-    std::vector<long long> table;      // start, end of every bucket (uploaded by eager_stats_attach)
+    std::vector<long long> table;      // start, end of every bucket (the device copy lives in the
+                                       // statistics workspace)
     eager::BucketStats *stats = nullptr;   // device, caller-owned; NULL: no by-products
     char *workspace = nullptr;             // device, caller-owned: bucket table, then records
     std::string err;
@@ -71,12 +72,13 @@ int64_t max_records(const eager_ctx *ctx)
 
 // Fills the parts of the statistics arguments that do not depend on the run: where the bucket
 // table, the records, the lane records and the partials live in the caller's workspace.
-void stats_layout(const eager_ctx *ctx, eager::StatsArgs &st)
+void stats_layout(const eager_ctx *ctx, char *workspace, eager::BucketStats *stats,
+                  eager::StatsArgs &st)
 {
-    st.table = reinterpret_cast<const long long *>(ctx->workspace);
-    st.stats = ctx->stats;
+    st.table = reinterpret_cast<const long long *>(workspace);
+    st.stats = stats;
     st.records = reinterpret_cast<eager::StatsRecord *>(
-        ctx->workspace + static_cast<size_t>(ctx->n_buckets) * 16);
+        workspace + static_cast<size_t>(ctx->n_buckets) * 16);
     st.lane_records = st.records + max_records(ctx);
     st.partials = st.lane_records + (static_cast<int64_t>(ctx->n_buckets) + 1) * 64;
     st.n_buckets = ctx->n_buckets;
@@ -104,10 +106,10 @@ bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t
     // to the reduction's reads cost 5-10 % of the round (P = 8, 7 late: 6.1 fused, 6.7 split).
     // The fused pass wins while few processes are late and all of its streams fit one chunk
     // of 16 loads, and on short runs, where the second launch costs more than it saves
-    // (25 M elements, P = 8: 7.03 fused against 6.82 TB/s split).  The rank-chunk kernel
-    // cannot drop the streams it does not need, and with bf16 gradients the fused pass is
-    // the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter configuration).
-    if (bf16 || l.compact == 0) return false;
+    // (25 M elements, P = 8: 7.03 fused against 6.82 TB/s split).  With bf16 gradients the
+    // fused pass is the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter
+    // configuration).
+    if (bf16) return false;
     const uint64_t late = ~mask & low_bits(P);
     const int n_late = popcount64(late);
     if (n_late == 0) return false;
@@ -191,9 +193,9 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
     a.nesterov = ctx->nesterov;
     const bool round_stats = ctx->stats && ctx->launch.round_stats;
     if (round_stats) {
-        if (ctx->launch.compact == 0 || (ctx->launch.chunk != 0 && ctx->launch.chunk != 16))
-            return fail(ctx, EAGER_ESTATE, "bucket statistics need compact = 1 and chunk = 16");
-        stats_layout(ctx, a.stats);
+        if (ctx->launch.chunk != 0 && ctx->launch.chunk != 16)
+            return fail(ctx, EAGER_ESTATE, "bucket statistics need the default chunk size (16)");
+        stats_layout(ctx, ctx->workspace, ctx->stats, a.stats);
     }
 
     // Consecutive buckets whose send buffers are in the same state form one run = one
@@ -207,9 +209,6 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         a.valid = ctx->valid[b];
         a.e0 = ctx->offset[b];
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
-        // stand-in address of the rank-chunk kernel: 16 readable bytes (the initiator is
-        // never absent, so its gradient exists)
-        a.dummy = static_cast<const char *>(grads[plan->initiator]) + a.e0 * (ctx->bf16 ? 2 : 4);
         const uint64_t late = ~plan->mask & ~absent & low_bits(P);   // finish a gradient late
         const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
         a.gload = split ? plan->mask : (plan->mask | late);
@@ -293,6 +292,11 @@ int eager_create(eager_ctx **out, int P, int n_buckets, const int64_t *bucket_of
         c->valid.assign(n_buckets, 0);
         c->last_step.assign(n_buckets, 0);
         c->stepped.assign(n_buckets, 0);
+        c->table.resize(static_cast<size_t>(n_buckets) * 2);
+        for (int b = 0; b < n_buckets; ++b) {
+            c->table[2 * b] = bucket_offset[b];
+            c->table[2 * b + 1] = bucket_offset[b] + bucket_numel[b];
+        }
     } catch (const std::bad_alloc &) {
         delete c;
         return EAGER_ENOMEM;
@@ -308,6 +312,11 @@ int eager_destroy(eager_ctx *ctx)
 }
 
 const char *eager_last_error(const eager_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+#ifndef EAGER_SOURCE_HASH
+#define EAGER_SOURCE_HASH "unknown"
+#endif
+const char *eager_source_hash(void) { return EAGER_SOURCE_HASH; }
 
 const char *eager_status_string(int status)
 {
@@ -478,19 +487,13 @@ int eager_sgd_step(eager_ctx *ctx, int b0, int b1, const float *update, const ea
     return EAGER_OK;
 }
 
-int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
-                        float trust, float eps, void *stream)
+namespace {
+// The layer-wise update with its statistics workspace at `workspace` and its per-bucket output
+// at `stats` (both device memory laid out as eager_stats_attach describes).
+int sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+                  float trust, float eps, char *workspace, eager::BucketStats *stats,
+                  void *stream)
 {
-    if (!ctx) return EAGER_EINVAL;
-    if (!update || !opt) return fail(ctx, EAGER_EINVAL, "update and opt must not be NULL");
-    if (!aligned16(update)) return fail(ctx, EAGER_EINVAL, "update must be 16-byte aligned");
-    if (!(trust > 0.0f) || std::isinf(trust) || !(eps >= 0.0f) || std::isinf(eps))
-        return fail(ctx, EAGER_EINVAL, "trust must be finite and > 0, eps finite and >= 0");
-    if (int st = check_range(ctx, b0, b1)) return st;
-    if (int st = check_opt(ctx, opt)) return st;
-    if (!ctx->stats)
-        return fail(ctx, EAGER_ESTATE, "the layer-wise rate needs eager_stats_attach (norms and rates "
-                                       "are written to the attached array)");
     eager::SgdArgs a;
     a.u = update;
     a.w = opt->params;
@@ -503,7 +506,7 @@ int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, con
     a.nesterov = ctx->nesterov;
     eager::StatsArgs st;
     std::memset(&st, 0, sizeof st);
-    stats_layout(ctx, st);
+    stats_layout(ctx, workspace, stats, st);
     st.slices = stats_slices(ctx, b0, b1);
     st.e0 = a.e0;
     st.b_lo = b0;
@@ -522,6 +525,29 @@ int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, con
         return fail(ctx, EAGER_EDEVICE, "layer-wise update launch failed: %s", hipGetErrorString(he));
     ctx->err.clear();
     return EAGER_OK;
+}
+
+int check_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+               float trust, float eps)
+{
+    if (!update || !opt) return fail(ctx, EAGER_EINVAL, "update and opt must not be NULL");
+    if (!aligned16(update)) return fail(ctx, EAGER_EINVAL, "update must be 16-byte aligned");
+    if (!(trust > 0.0f) || std::isinf(trust) || !(eps >= 0.0f) || std::isinf(eps))
+        return fail(ctx, EAGER_EINVAL, "trust must be finite and > 0, eps finite and >= 0");
+    if (int st = check_range(ctx, b0, b1)) return st;
+    return check_opt(ctx, opt);
+}
+}  // namespace
+
+int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
+                        float trust, float eps, void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (int st = check_lars(ctx, b0, b1, update, opt, trust, eps)) return st;
+    if (!ctx->stats)
+        return fail(ctx, EAGER_ESTATE, "the layer-wise rate needs eager_stats_attach (norms and rates "
+                                       "are written to the attached array)");
+    return sgd_step_lars(ctx, b0, b1, update, opt, trust, eps, ctx->workspace, ctx->stats, stream);
 }
 
 namespace {
@@ -632,15 +658,6 @@ int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspac
                     static_cast<long long>(need));
     if (!aligned16(stats) || !aligned16(workspace))
         return fail(ctx, EAGER_EINVAL, "stats and workspace must be 16-byte aligned");
-    try {
-        ctx->table.resize(static_cast<size_t>(ctx->n_buckets) * 2);
-    } catch (const std::bad_alloc &) {
-        return fail(ctx, EAGER_ENOMEM, "out of host memory");
-    }
-    for (int b = 0; b < ctx->n_buckets; ++b) {
-        ctx->table[2 * b] = ctx->offset[b];
-        ctx->table[2 * b + 1] = ctx->offset[b] + ctx->numel[b];
-    }
     // the table lives in the context, so it outlives the copy
     hipError_t he = hipMemcpyAsync(workspace, ctx->table.data(), ctx->table.size() * 8,
                                    hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
@@ -670,25 +687,12 @@ int eager_set_launch(eager_ctx *ctx, const char *key, int value)
         if (value != 64 && value != 128 && value != 256)
             return fail(ctx, EAGER_EINVAL, "block must be 64, 128 or 256");
         ctx->launch.block = value;
-    } else if (!std::strcmp(key, "max_blocks")) {
-        if (value < 0) return fail(ctx, EAGER_EINVAL, "max_blocks must be >= 0");
-        ctx->launch.max_blocks = value;
-    } else if (!std::strcmp(key, "unroll")) {
-        if (value != 1 && value != 2)
-            return fail(ctx, EAGER_EINVAL, "unroll must be 1 or 2");
-        ctx->launch.unroll = value;
-    } else if (!std::strcmp(key, "nontemporal")) {
-        if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "nontemporal must be 0 or 1");
-        ctx->launch.nontemporal = value;
-    } else if (!std::strcmp(key, "compact")) {
-        if (value != 0 && value != 1) return fail(ctx, EAGER_EINVAL, "compact must be 0 or 1");
-        ctx->launch.compact = value;
     } else if (!std::strcmp(key, "split")) {
         if (value < 0 || value > 2) return fail(ctx, EAGER_EINVAL, "split must be 0, 1 or 2");
         ctx->launch.split = value;
     } else if (!std::strcmp(key, "chunk")) {
-        if (value != 0 && value != 4 && value != 8 && value != 16 && value != 32)
-            return fail(ctx, EAGER_EINVAL, "chunk must be 0, 4, 8, 16 or 32");
+        if (value != 0 && value != 8 && value != 16)
+            return fail(ctx, EAGER_EINVAL, "chunk must be 0, 8 or 16");
         ctx->launch.chunk = value;
     } else if (!std::strcmp(key, "blocks_per_cu")) {
         if (value < -1 || value > 32) return fail(ctx, EAGER_EINVAL, "blocks_per_cu must be -1..32");

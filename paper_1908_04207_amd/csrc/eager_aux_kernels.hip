@@ -546,7 +546,7 @@ hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_
     if (a.n <= 0) return hipSuccess;
     // 64-thread workgroups, one lane-vector per lane unless the grid is capped (measured on
     // 355 M elements: 1.12 ms against 1.22 ms with 256-thread workgroups and cached state)
-    const dim3 grid(grid_for(a.n / 4, 64, cfg.max_blocks)), block(64);
+    const dim3 grid(grid_for(a.n / 4, 64, 0)), block(64);
     const bool nt = a.n * 8 > kStateCacheBytes;
     if (fast) {
         if (nt) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, block, 0, stream, a);

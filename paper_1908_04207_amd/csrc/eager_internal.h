@@ -62,11 +62,11 @@ struct RoundArgs {
     float *r[kMaxP];             // R_p arena bases (fp32)
     unsigned long long active;   // bit p: process p is on time in this round
     unsigned long long valid;    // bit p: R_p holds an undelivered gradient
-    unsigned long long gload;    // bit p: this launch reads G_p (all p < P when fused; only
-                                 // on-time processes when the carry runs as its own kernel)
+    unsigned long long gload;    // bit p: this launch reads G_p (every process that has a gradient
+                                 // when fused; only on-time processes when the carry runs as
+                                 // its own kernel)
     unsigned long long store;    // bit p: this launch stores G_p into R_p (late processes when
                                  // fused; none otherwise)
-    const void *dummy;           // 16 readable bytes: stands in for streams not to be read
     float *w;                    // parameters (NULL: no update rule)
     float *v;                    // momentum
     float *recv;                 // receive buffer (NULL: not wanted)
@@ -155,15 +155,10 @@ struct SgdArgs {
 
 struct Launch {
     int block = 64;        // threads per workgroup
-    int max_blocks = 0;    // 0: one workgroup per tile
-    int unroll = 1;        // 16-byte vectors per thread and iteration
-    int nontemporal = 1;   // streaming hints on G and R
-    int chunk = 0;         // ranks whose loads are in flight together; 0: chosen from P
-    int compact = 1;       // 1 = compacted stream list (slot kernel), 0 = rank chunks with
-                           // stand-in loads (the earlier form, kept for comparison)
+    int chunk = 0;         // streams whose loads are in flight together; 0: 16
     int split = 0;         // 0: chosen from the round; 1: one fused kernel; 2: reduce+update
                            // kernel followed by a carry (copy) kernel
-    int blocks_per_cu = 0; // 0: chosen from P; -1: no cap; else max workgroups resident per CU
+    int blocks_per_cu = 0; // 0: chosen from the round; -1: no cap; else max workgroups resident per CU
     int nt_state = -1;     // w, v, recv nontemporal: -1 chosen from their size, 0 no, 1 yes
     int xcd_map = 0;       // slot kernel: 1 = contiguous eighth of the run per XCD
     int carry_block = 64;  // carry kernel: threads per workgroup
@@ -174,9 +169,6 @@ struct Launch {
 
 hipError_t launch_round(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
                         hipStream_t stream);
-// the rank-chunk form of the round ("compact" = 0)
-hipError_t launch_round_chunks(const RoundArgs &a, bool bf16, bool fast, const Launch &cfg,
-                               hipStream_t stream);
 hipError_t launch_carry(const CarryArgs &a, bool bf16, const Launch &cfg, hipStream_t stream);
 hipError_t launch_stats_finish(const StatsArgs &a, hipStream_t stream);
 long long slot_records(long long n, bool bf16, int block);   // wavefronts of a slot launch

@@ -357,27 +357,22 @@ def test_unfused_pair_equals_fused(eb):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_launch_shapes_give_identical_bits(eb, dtype):
-    """Block size, vectors per thread, capped (striding) grids and cache hints change
-    nothing in the result."""
+    """Block size, chunk size, occupancy caps, the split form and cache
+    hints change nothing in the result."""
     cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 3), 40000)
     bt = cfg.buckets
     ref = None
     shapes_ = [
-        dict(block=256, unroll=1, max_blocks=0, nontemporal=1, chunk=0, blocks_per_cu=0, split=1,
-             compact=1),
-        dict(block=64, unroll=2, max_blocks=0, nontemporal=1, chunk=4, blocks_per_cu=4, split=2,
-             compact=0),
-        dict(block=128, unroll=1, max_blocks=3, nontemporal=0, chunk=16, blocks_per_cu=2, split=1,
-             compact=1, nt_state=0),
-        dict(block=256, unroll=1, max_blocks=0, nontemporal=1, chunk=16, blocks_per_cu=1, split=2,
-             compact=1, nt_state=1, carry_block=256, carry_vec=4, carry_blocks_per_cu=2),
-        dict(block=256, unroll=2, max_blocks=7, nontemporal=0, chunk=8, blocks_per_cu=3, split=0,
-             compact=1, carry_block=128, carry_vec=2),
-        dict(block=64, unroll=2, max_blocks=0, nontemporal=1, chunk=8, blocks_per_cu=-1, split=2,
-             compact=1, carry_vec=2, carry_blocks_per_cu=32, xcd_map=1),
-        dict(block=128, chunk=32, split=1, compact=1, xcd_map=1),
-        dict(block=64, unroll=1, max_blocks=2, nontemporal=1, chunk=32 if dtype == "f32" else 16,
-             blocks_per_cu=5, split=2, compact=0, carry_block=64, carry_vec=4)]
+        dict(block=256, chunk=0, blocks_per_cu=0, split=1),
+        dict(block=64, chunk=8, blocks_per_cu=4, split=2),
+        dict(block=128, chunk=16, blocks_per_cu=2, split=1, nt_state=0),
+        dict(block=256, chunk=16, blocks_per_cu=1, split=2, nt_state=1, carry_block=256,
+             carry_vec=4, carry_blocks_per_cu=2),
+        dict(block=256, chunk=8, blocks_per_cu=3, split=0, carry_block=128, carry_vec=2),
+        dict(block=64, chunk=8, blocks_per_cu=-1, split=2, carry_vec=2, carry_blocks_per_cu=32,
+             xcd_map=1),
+        dict(block=128, chunk=16, split=1, xcd_map=1),
+        dict(block=64, blocks_per_cu=5, split=2, carry_block=64, carry_vec=4)]
     for launch in shapes_:
         pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, seed=4)
         for key, val in launch.items():
@@ -392,8 +387,8 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
 
 
 @pytest.mark.parametrize("dtype,launch,order", [
-    ("f32", {}, 0), ("f32", {"split": 1}, 0), ("f32", {"split": 2}, 0), ("f32", {"compact": 0}, 0),
-    ("bf16", {}, 0), ("bf16", {"compact": 0, "split": 2}, 0), ("f32", {}, 1), ("bf16", {}, 1)])
+    ("f32", {}, 0), ("f32", {"split": 1}, 0), ("f32", {"split": 2}, 0), ("f32", {"chunk": 8}, 0),
+    ("bf16", {}, 0), ("bf16", {"chunk": 8, "split": 2}, 0), ("f32", {}, 1), ("bf16", {}, 1)])
 def test_lagging_processes_and_stashed_gradients(eb, dtype, launch, order):
     """Processes that lag by more than one round (Section 5, last paragraph): in a round they
     are neither on time nor late - they store nothing - and the gradients they finish between
@@ -695,12 +690,12 @@ def test_nothing_is_written_outside_the_buffers(eb, dtype):
         inside[place[(name, p)]:place[(name, p)] + arena * size] = True
     rng = np.random.default_rng(3)
     nb = len(numel)
-    for launch in ({}, {"split": 2}, {"split": 1, "chunk": 8}, {"compact": 0, "unroll": 2},
+    for launch in ({}, {"split": 2}, {"split": 1, "chunk": 8}, {"split": 2, "chunk": 8},
                    {"block": 256, "blocks_per_cu": 1, "xcd_map": 1}):
         ctx = eb.Context(P, off, numel, eb.BF16 if dtype == "bf16" else eb.F32, eb.ORDER_FIXED)
         for key, val in launch.items():
             ctx.eager_set_launch(key, val)
-        use_stats = launch.get("compact", 1) == 1 and launch.get("chunk", 0) in (0, 16)
+        use_stats = launch.get("chunk", 0) in (0, 16)
         if use_stats:
             stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
             nbytes = ctx.eager_stats_workspace_bytes()
@@ -803,15 +798,12 @@ def test_seeded_random_cases_bitwise(eb, seed):
     launch = {}
     if rng.integers(0, 2):
         launch["split"] = int(rng.integers(0, 3))
-    if rng.integers(0, 3) == 0:
-        launch["compact"] = 0
-    else:
-        if rng.integers(0, 2):
-            launch["chunk"] = int(rng.choice([8, 16]))
-        if rng.integers(0, 2):
-            launch["block"] = int(rng.choice([64, 128, 256]))
-        if rng.integers(0, 2):
-            launch["xcd_map"] = 1
+    if rng.integers(0, 2):
+        launch["chunk"] = int(rng.choice([8, 16]))
+    if rng.integers(0, 2):
+        launch["block"] = int(rng.choice([64, 128, 256]))
+    if rng.integers(0, 2):
+        launch["xcd_map"] = 1
     if rng.integers(0, 2):
         launch["blocks_per_cu"] = int(rng.choice([-1, 1, 3, 8]))
     if rng.integers(0, 2):

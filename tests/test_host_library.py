@@ -252,7 +252,7 @@ def test_other_entry_points_validate_on_the_host():
     refused(eb.EINVAL, lambda: c.eager_stats_attach(0x400000, 0, need, stream=0))
     c.eager_stats_attach(None, None, stream=0)         # detaching what is not attached is fine
     for key, bad in (("round_stats", 2), ("split", 3), ("nt_state", 2), ("xcd_map", -1), ("chunk", 5),
-                     ("blocks_per_cu", 33), ("carry_vec", 3), ("compact", 2)):
+                     ("blocks_per_cu", 33), ("carry_vec", 3), ("compact", 1)):
         refused(eb.EINVAL, lambda: c.eager_set_launch(key, bad))
     refused(eb.EINVAL, lambda: c.eager_set_update_rule(float("nan"), False))
     c.close()
