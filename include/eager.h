@@ -54,7 +54,8 @@ typedef enum {
     EAGER_ESTATE = 3,    /* plan does not fit the context or the entry point, or a bucket is
                             given the same round twice                                           */
     EAGER_EDEVICE = 4,   /* a HIP call or a kernel launch failed                                 */
-    EAGER_ENOMEM = 5     /* host allocation failed                                               */
+    EAGER_ENOMEM = 5,    /* host allocation failed                                               */
+    EAGER_ELIMIT = 6     /* beyond the fixed capacity of the entry point that allocates nothing  */
 } eager_status;
 
 #define EAGER_MAX_P 64
@@ -287,6 +288,33 @@ int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspac
  */
 int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
                         float trust, float eps, void *stream);
+
+/*
+ * eager_sgd_step_lars for callers that cannot allocate device memory at all - code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc - and so cannot bring the
+ * workspace that eager_stats_attach wants.  Same kernels and the same results bit for bit; the
+ * workspace (bucket table, per-wavefront records, partials) is a fixed device array inside the
+ * library instead, EAGER_STATIC_SCRATCH_BYTES per GPU, held until the process ends.  The call
+ * allocates, frees and copies nothing: the bucket table is written by a small kernel from the
+ * kernel arguments.  No eager_stats_attach is needed (an attached workspace is left alone).
+ *   stats   device array of n_buckets entries, 16-byte aligned, caller-owned: receives
+ *           sumsq_update, sumsq_params (before the step), nonfinite and rate of every bucket in
+ *           [b0, b1)
+ * Limits: a context of at most EAGER_STATIC_MAX_BUCKETS buckets whose arena spans at most
+ * EAGER_STATIC_MAX_ELEMENTS elements (first bucket start to last bucket end); beyond that the
+ * call returns EAGER_ELIMIT and launches nothing.
+ * All calls on one GPU share the array and it keeps the last call's contents (every record that
+ * is read has been written by the same call before, so nothing needs clearing): calls that
+ * overlap in time on one GPU - two streams, two contexts, two threads - race; order them.
+ * Errors: as eager_sgd_step_lars without ESTATE; EINVAL also for a NULL or misaligned stats;
+ * ELIMIT; EDEVICE.
+ */
+#define EAGER_STATIC_MAX_BUCKETS 512
+#define EAGER_STATIC_MAX_ELEMENTS (1ll << 27)
+#define EAGER_STATIC_SCRATCH_BYTES 18884864ll
+int eager_sgd_step_lars_static(eager_ctx *ctx, int b0, int b1, const float *update,
+                               const eager_opt *opt, float trust, float eps,
+                               eager_bucket_stats *stats, void *stream);
 
 /* Send-buffer validity of one bucket (bit p: R_p holds an undelivered gradient);
  * together with w, v, R and the round index this is all the state a resume needs. */

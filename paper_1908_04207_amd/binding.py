@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(HERE, "libeager.so")
 SOLO, MAJORITY, QUORUM = 0, 1, 2
 F32, BF16 = 0, 1
 ORDER_FIXED, ORDER_FAST = 0, 1
-OK, EINVAL, ESHAPE, ESTATE, EDEVICE, ENOMEM = range(6)
+OK, EINVAL, ESHAPE, ESTATE, EDEVICE, ENOMEM, ELIMIT = range(7)
+STATIC_MAX_BUCKETS, STATIC_MAX_ELEMENTS = 512, 1 << 27
 FLAG_STRICT_QUORUM = 1
 MAX_P = 64
 
@@ -26,7 +27,7 @@ EXPORTS = (
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
     "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
-    "eager_sgd_step_views",
+    "eager_sgd_step_lars_static", "eager_sgd_step_views",
     "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
@@ -91,6 +92,8 @@ def _load() -> ctypes.CDLL:
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
     lib.eager_sgd_step_lars.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), ctypes.c_float,
                                         ctypes.c_float, vp]
+    lib.eager_sgd_step_lars_static.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt),
+                                               ctypes.c_float, ctypes.c_float, vp, vp]
     lib.eager_sgd_step_views.argtypes = [vp, i32, i32, vp, i32, ctypes.POINTER(vp),
                                          ctypes.POINTER(vp), ctypes.c_float, ctypes.c_float, vp]
     lib.eager_average_views.argtypes = [vp, i32, i32, i32, ctypes.POINTER(vp), vp]
@@ -263,6 +266,17 @@ class Context:
         o = Opt(_ptr(params), _ptr(momentum), lr, mu)
         self._check(lib.eager_sgd_step_lars(self._h, b0, b1, _ptr(update), ctypes.byref(o), trust,
                                             eps, _stream(stream)), "eager_sgd_step_lars")
+
+    def eager_sgd_step_lars_static(self, update, opt, trust: float, stats, eps: float = 0.0,
+                                   b0: int = 0, b1: Optional[int] = None, stream=None) -> None:
+        """The layer-wise update with the library's fixed scratch as workspace; `stats` is the
+        device buffer of n_buckets x 32 bytes that receives norms and rates."""
+        b1 = self.n_buckets if b1 is None else b1
+        params, momentum, lr, mu = opt
+        o = Opt(_ptr(params), _ptr(momentum), lr, mu)
+        self._check(lib.eager_sgd_step_lars_static(self._h, b0, b1, _ptr(update), ctypes.byref(o),
+                                                   trust, eps, _ptr(stats), _stream(stream)),
+                    "eager_sgd_step_lars_static")
 
     def eager_sgd_step_views(self, update, params, momentum, lr: float, mu: float, b0: int = 0,
                              b1: Optional[int] = None, stream=None) -> None:

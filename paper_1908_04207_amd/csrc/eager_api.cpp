@@ -327,6 +327,7 @@ const char *eager_status_string(int status)
     case EAGER_ESTATE: return "EAGER_ESTATE";
     case EAGER_EDEVICE: return "EAGER_EDEVICE";
     case EAGER_ENOMEM: return "EAGER_ENOMEM";
+    case EAGER_ELIMIT: return "EAGER_ELIMIT";
     default: return "EAGER_<unknown>";
     }
 }
@@ -492,7 +493,7 @@ namespace {
 // at `stats` (both device memory laid out as eager_stats_attach describes).
 int sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eager_opt *opt,
                   float trust, float eps, char *workspace, eager::BucketStats *stats,
-                  void *stream)
+                  bool fill_table, void *stream)
 {
     eager::SgdArgs a;
     a.u = update;
@@ -518,7 +519,11 @@ int sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, const eag
     st.wd = ctx->weight_decay;
     st.eps = eps;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t he = eager::launch_norms(a, st, s);
+    hipError_t he = hipSuccess;
+    if (fill_table)
+        he = eager::launch_table_fill(reinterpret_cast<long long *>(workspace), ctx->table.data(),
+                                      ctx->n_buckets, s);
+    if (he == hipSuccess) he = eager::launch_norms(a, st, s);
     if (he == hipSuccess) he = eager::launch_stats_finish(st, s);
     if (he == hipSuccess) he = eager::launch_sgd_lars(a, st, ctx->fast, s);
     if (he != hipSuccess)
@@ -547,7 +552,40 @@ int eager_sgd_step_lars(eager_ctx *ctx, int b0, int b1, const float *update, con
     if (!ctx->stats)
         return fail(ctx, EAGER_ESTATE, "the layer-wise rate needs eager_stats_attach (norms and rates "
                                        "are written to the attached array)");
-    return sgd_step_lars(ctx, b0, b1, update, opt, trust, eps, ctx->workspace, ctx->stats, stream);
+    return sgd_step_lars(ctx, b0, b1, update, opt, trust, eps, ctx->workspace, ctx->stats, false,
+                         stream);
+}
+
+int eager_sgd_step_lars_static(eager_ctx *ctx, int b0, int b1, const float *update,
+                               const eager_opt *opt, float trust, float eps,
+                               eager_bucket_stats *stats, void *stream)
+{
+    static_assert(EAGER_STATIC_MAX_BUCKETS == eager::kStaticMaxBuckets &&
+                      EAGER_STATIC_MAX_ELEMENTS == eager::kStaticMaxElements &&
+                      EAGER_STATIC_SCRATCH_BYTES == eager::kStaticScratchBytes,
+                  "the header states the capacity of the fixed scratch");
+    if (!ctx) return EAGER_EINVAL;
+    if (int st = check_lars(ctx, b0, b1, update, opt, trust, eps)) return st;
+    if (!stats || !aligned16(stats))
+        return fail(ctx, EAGER_EINVAL, "stats must be a 16-byte aligned device array of n_buckets entries");
+    const int64_t span = ctx->offset.back() + ctx->numel.back() - ctx->offset.front();
+    if (ctx->n_buckets > eager::kStaticMaxBuckets || span > eager::kStaticMaxElements)
+        return fail(ctx, EAGER_ELIMIT,
+                    "the library's fixed scratch holds the statistics of at most %d buckets spanning "
+                    "%lld elements; this context has %d buckets spanning %lld (use eager_stats_attach "
+                    "and eager_sgd_step_lars with a workspace of your own)",
+                    eager::kStaticMaxBuckets, static_cast<long long>(eager::kStaticMaxElements),
+                    ctx->n_buckets, static_cast<long long>(span));
+    int64_t need = 0;
+    eager_stats_workspace_bytes(ctx, &need);
+    if (need > eager::kStaticScratchBytes)     // cannot happen within the two limits above
+        return fail(ctx, EAGER_ELIMIT, "statistics workspace of %lld bytes exceeds the fixed scratch",
+                    static_cast<long long>(need));
+    char *scratch = nullptr;
+    if (hipError_t he = eager::static_scratch(&scratch); he != hipSuccess)
+        return fail(ctx, EAGER_EDEVICE, "address of the fixed scratch: %s", hipGetErrorString(he));
+    return sgd_step_lars(ctx, b0, b1, update, opt, trust, eps, scratch,
+                         reinterpret_cast<eager::BucketStats *>(stats), true, stream);
 }
 
 namespace {

@@ -54,6 +54,25 @@ struct StatsArgs {
 constexpr int kStatsMaxSlices = 64;
 constexpr long long kStatsRecordsPerSlice = 4096;
 
+// Capacity of the entry point that allocates nothing: its statistics workspace is a fixed
+// device array inside the library (bucket table, one record per 256 elements, lane records,
+// partials - the layout of the caller-provided workspace), so the context may hold at most this
+// many buckets and span at most this many elements.
+constexpr int kStaticMaxBuckets = 512;
+constexpr long long kStaticMaxElements = 1ll << 27;
+constexpr long long kStaticMaxRecords = kStaticMaxElements / 256 + 8;
+constexpr long long kStaticScratchBytes =
+    kStaticMaxBuckets * 16ll +
+    (kStaticMaxRecords + (kStaticMaxBuckets + 1ll) * 64 + kStaticMaxBuckets * 1ll * kStatsMaxSlices) * 32;
+
+// Bucket table entries handed to the device in one kernel-argument block.
+constexpr int kTableChunk = 120;
+struct TableArgs {
+    long long *table;            // device: start, end of every bucket
+    int first, count;            // buckets [first, first + count) are written
+    long long start_end[2 * kTableChunk];
+};
+
 // Everything one launch of the round kernel needs, passed by value in the kernel
 // argument segment: the P gradient and send-buffer bases stay in scalar registers and
 // every per-rank decision is uniform across the grid.
@@ -182,6 +201,12 @@ hipError_t launch_sgd(const SgdArgs &a, bool fast, const Launch &cfg, hipStream_
 hipError_t launch_norms(const SgdArgs &a, const StatsArgs &st, hipStream_t stream);
 hipError_t launch_sgd_lars(const SgdArgs &a, const StatsArgs &st, bool fast, hipStream_t stream);
 long long norms_records(long long n);
+// This device's copy of the library's fixed scratch array (kStaticScratchBytes bytes, 256-byte
+// aligned); the address is looked up once per device.  launch_table_fill writes the bucket
+// table there with a kernel, so that the call needs no host-to-device copy.
+hipError_t static_scratch(char **ptr);
+hipError_t launch_table_fill(long long *table, const long long *start_end, int n_buckets,
+                             hipStream_t stream);
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);
 

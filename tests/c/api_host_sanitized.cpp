@@ -89,6 +89,19 @@ hipError_t launch_sgd(const SgdArgs &a, bool, const Launch &, hipStream_t) { ret
 hipError_t launch_norms(const SgdArgs &a, const StatsArgs &, hipStream_t) { return sgd("norms", a); }
 hipError_t launch_sgd_lars(const SgdArgs &a, const StatsArgs &, bool, hipStream_t) { return sgd("lars", a); }
 long long norms_records(long long n) { return n / 256 + 4; }
+static char g_scratch[64];
+hipError_t static_scratch(char **ptr) { *ptr = g_scratch; return hipSuccess; }
+hipError_t launch_table_fill(long long *table, const long long *start_end, int n_buckets, hipStream_t)
+{
+    Launched l;
+    l.kind = "table";
+    l.count = n_buckets;
+    // the host copy of the table is read here, under the sanitizers
+    for (int i = 0; i < 2 * n_buckets; ++i) l.n += start_end[i];
+    l.has_w = reinterpret_cast<char *>(table) == g_scratch;
+    g_log.push_back(l);
+    return hipSuccess;
+}
 hipError_t launch_copy(void *, const void *, long long, hipStream_t) { return hipSuccess; }
 hipError_t launch_read(const void *, long long, float *, hipStream_t) { return hipSuccess; }
 }  // namespace eager
@@ -216,6 +229,16 @@ int main()
     CHECK(g_log.size() == 3 && g_log[0].kind == "norms" && g_log[1].kind == "finish" && g_log[2].kind == "lars");
     CHECK(g_log[0].e0 == 8 && g_log[0].n == 1008 && g_log[1].b_lo == 1 && g_log[1].b_hi == 3 && g_log[2].n == 1008);
     CHECK(eager_sgd_step_lars(ctx, 1, 3, recv, &opt, -1.0f, 0.0f, nullptr) == EAGER_EINVAL);
+    // the same rule with the library's fixed scratch as workspace: the bucket table is written by
+    // a kernel first, nothing needs to be attached, and the attached workspace is left alone
+    g_log.clear();
+    CHECK(eager_sgd_step_lars_static(ctx, 1, 3, recv, &opt, 0.02f, 1e-9f, stats, nullptr) == EAGER_OK);
+    CHECK(g_log.size() == 4 && g_log[0].kind == "table" && g_log[0].count == NB && g_log[0].has_w &&
+          g_log[0].n == 0 + 5 + 8 + 16 + 16 + 1016 + 1024 + 1064);
+    CHECK(g_log[1].kind == "norms" && g_log[2].kind == "finish" && g_log[3].kind == "lars" && g_log[3].n == 1008);
+    CHECK(eager_sgd_step_lars_static(ctx, 1, 3, recv, &opt, 0.02f, 1e-9f, nullptr, nullptr) == EAGER_EINVAL);
+    CHECK(eager_sgd_step_lars_static(ctx, 3, 1, recv, &opt, 0.02f, 1e-9f, stats, nullptr) == EAGER_EINVAL);
+    CHECK(g_log.size() == 4);
     // by-products switched off for rounds: the round alone
     g_log.clear();
     CHECK(eager_set_launch(ctx, "round_stats", 0) == EAGER_OK);
@@ -235,7 +258,25 @@ int main()
     eager_plan p6 = plan_of(EAGER_MAJORITY, 2, 0, 0b01, 0);
     CHECK(eager_partial_allreduce_majority(ctx, &p6, 0, 1, G, R, nullptr, &opt, nullptr) == EAGER_OK);
     CHECK(g_log.size() == 2 && g_log[1].kind == "finish" && g_log[1].count == eager::kStatsMaxSlices);
+    // beyond the capacity of the fixed scratch: refused, nothing launched
+    g_log.clear();
+    CHECK(eager_sgd_step_lars_static(ctx, 0, 1, recv, &opt, 0.02f, 0.0f, stats, nullptr) == EAGER_ELIMIT);
+    CHECK(g_log.empty() && std::string(eager_last_error(ctx)).find("fixed scratch") != std::string::npos);
     CHECK(eager_destroy(ctx) == EAGER_OK);
+    {
+        std::vector<int64_t> many_off(EAGER_STATIC_MAX_BUCKETS + 1), many_num(EAGER_STATIC_MAX_BUCKETS + 1, 4);
+        for (size_t b = 0; b < many_off.size(); ++b) many_off[b] = 4 * static_cast<int64_t>(b);
+        CHECK(eager_create(&ctx, 2, EAGER_STATIC_MAX_BUCKETS + 1, many_off.data(), many_num.data(), EAGER_F32,
+                           EAGER_ORDER_FIXED) == EAGER_OK);
+        CHECK(eager_sgd_step_lars_static(ctx, 0, 1, recv, &opt, 0.02f, 0.0f, stats, nullptr) == EAGER_ELIMIT);
+        CHECK(eager_destroy(ctx) == EAGER_OK);
+        CHECK(eager_create(&ctx, 2, EAGER_STATIC_MAX_BUCKETS, many_off.data(), many_num.data(), EAGER_F32,
+                           EAGER_ORDER_FIXED) == EAGER_OK);
+        CHECK(eager_sgd_step_lars_static(ctx, 0, EAGER_STATIC_MAX_BUCKETS, recv, &opt, 0.02f, 0.0f, stats, nullptr) ==
+              EAGER_OK);
+        CHECK(g_log.size() == 4 && g_log[0].count == EAGER_STATIC_MAX_BUCKETS);
+        CHECK(eager_destroy(ctx) == EAGER_OK);
+    }
 
     // creation errors leave nothing behind
     const int64_t bad_off[2] = {0, 2}, bad_num[2] = {2, 4};
