@@ -321,49 +321,6 @@ int eager_sgd_step_lars_static(eager_ctx *ctx, int b0, int b1, const float *upda
 int eager_get_valid(const eager_ctx *ctx, int bucket, uint64_t *valid_mask);
 int eager_set_valid(eager_ctx *ctx, int bucket, uint64_t valid_mask);
 
-/*
- * Launch shape of the round kernels, for measurement sweeps.  Unknown keys: EINVAL.  A
- * combination the library has no kernel for makes the next round fail with EDEVICE.
- *   "compact"    1 (default) = only the streams a round needs are listed and read (one
- *                group of 4 elements per lane, grid covers the range; "unroll",
- *                "max_blocks" and "nontemporal" do not apply, "chunk" is 8, 16 (default)
- *                or 32);
- *                0 = fixed rank chunks with cached stand-in loads
- *   "split"      0 = chosen per round (default: fp32 gradients on the compact path are split
- *                when 8 or more processes are late, or when somebody is late and the fused
- *                pass would have more than 16 streams); 1 = one fused kernel; 2 = reduction +
- *                update kernel followed by a copy kernel for the send buffers of late processes
- *   "nt_state"   compact path: nontemporal hint on w, v and recv too: -1 (default) = when
- *                they exceed 256 MiB in the call (they cannot stay in the last-level cache
- *                until the next round), 0 = never, 1 = always
- *   "xcd_map"    compact path: 0 (default) = consecutive workgroups, which the hardware deals
- *                to the 8 XCDs round robin, take consecutive tiles; 1 = every XCD takes one
- *                contiguous eighth of the range (measured 2.5 % slower: kept for A/B)
- *   "carry_block", "carry_vec", "carry_blocks_per_cu"  shape of the copy kernel of a split
- *                round: threads per workgroup (64 default, 128, 256), groups of 4 elements
- *                per thread (1 default, 2, 4), resident workgroups per CU (-1 = no cap,
- *                default; 1..32)
- *   "round_stats" 1 (default) = with statistics attached every round writes the by-products;
- *                0 = rounds leave them alone (for callers that attach the statistics only as
- *                the workspace of eager_sgd_step_lars, which forms its own norms)
- *   "block"      threads per workgroup: 64 (default), 128 or 256
- *   "blocks_per_cu" 0 = chosen from the round (default); -1 = no cap; 1..32 = at most
- *                that many workgroups resident per CU
- *   "chunk"      streams (ranks) whose loads are in flight together: 0 = default, 4, 8, 16,
- *                32 (32 and, with bf16 gradients and unroll 2, 16 exist only in part)
- *   "max_blocks" rank-chunk kernel: 0 = one workgroup per tile; otherwise a cap,
- *                workgroups then stride
- *   "unroll"     rank-chunk kernel: 16-byte vectors per thread and iteration: 1 or 2
- *   "nontemporal" rank-chunk kernel: 1 = streaming cache hints on G and R, 0 = plain
- */
-int eager_set_launch(eager_ctx *ctx, const char *key, int value);
-
-/* Plain streaming kernels of known traffic, to calibrate bandwidth and the profiler's
- * byte counters against the round kernel.  nbytes must be a multiple of 16, pointers
- * 16-byte aligned device memory.  copy: dst <- src.  read: sums src into *sink. */
-int eager_calib_copy(void *dst, const void *src, int64_t nbytes, void *stream);
-int eager_calib_read(const void *src, int64_t nbytes, float *sink, void *stream);
-
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTS = (
     "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
     "eager_set_valid", "eager_set_launch", "eager_calib_copy", "eager_calib_read",
+    "eager_calib_mix",
 )
 
 
@@ -105,6 +106,8 @@ def _load() -> ctypes.CDLL:
     lib.eager_stats_attach.argtypes = [vp, vp, vp, i64, vp]
     lib.eager_calib_copy.argtypes = [vp, vp, i64, vp]
     lib.eager_calib_read.argtypes = [vp, i64, vp, vp]
+    lib.eager_calib_mix.argtypes = [ctypes.POINTER(vp), i32, u64, ctypes.POINTER(vp), i32, i64, i32,
+                                    vp, vp]
     return lib
 
 
@@ -329,3 +332,16 @@ def eager_calib_read(src, nbytes: int, sink, stream=None) -> None:
     st = lib.eager_calib_read(_ptr(src), nbytes, _ptr(sink), _stream(stream))
     if st != OK:
         raise EagerError(st, f"eager_calib_read: {status_string(st)}")
+
+
+def eager_calib_mix(read, write, n_vec: int, read_half_mask: int = 0, waves_per_cu: int = 0,
+                    sink=None, stream=None) -> None:
+    """A plain kernel that reads len(read) streams and writes len(write) streams (n_vec
+    16-byte lane-vectors each).  `read` and `write` are lists of device buffers or pointer
+    tables from Context.pointers."""
+    r = read if isinstance(read, ctypes.Array) else Context.pointers(read)
+    w = write if isinstance(write, ctypes.Array) else Context.pointers(write)
+    st = lib.eager_calib_mix(r, len(read), read_half_mask, w, len(write), n_vec, waves_per_cu,
+                             _ptr(sink), _stream(stream))
+    if st != OK:
+        raise EagerError(st, f"eager_calib_mix: {status_string(st)}")

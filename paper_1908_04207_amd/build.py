@@ -21,7 +21,7 @@ LIB = os.path.join(HERE, "libeager.so")
 STAMP = LIB + ".srchash"
 OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ["eager_round_kernels.hip", "eager_aux_kernels.hip", "eager_static_kernels.hip",
-           "eager_api.cpp"]
+           "eager_calib_kernels.hip", "eager_api.cpp"]
 
 # -ffp-contract=off: the fixed-order mode defines every rounding; fused multiply-adds are
 # written out where they are meant.  Packed fp32 instructions are switched off: a feature of

@@ -1,7 +1,7 @@
 // Host side of the C ABI: context state (bucket table, send-buffer validity per bucket),
 // argument checking, the participation plan, and the split of a bucket range into runs
 // that one kernel launch each can cover.  All arithmetic of a round runs in the kernels.
-#include "../../include/eager.h"
+#include "../../include/eager_tuning.h"
 #include "eager_internal.h"
 
 #include <algorithm>
@@ -774,6 +774,35 @@ int eager_calib_read(const void *src, int64_t nbytes, float *sink, void *stream)
 {
     if (!src || !sink || nbytes < 0 || nbytes % 16 || !aligned16(src)) return EAGER_EINVAL;
     return eager::launch_read(src, nbytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? EAGER_OK : EAGER_EDEVICE;
+}
+
+int eager_calib_mix(const void *const *read, int n_read, uint64_t read_half_mask,
+                    void *const *write, int n_write, int64_t n_vec, int waves_per_cu, float *sink,
+                    void *stream)
+{
+    if (!read || n_read < 1 || n_read > eager::kMixMaxRead || n_write < 0 ||
+        n_write > eager::kMixMaxWrite || (n_write > 0 && !write) || (n_write == 0 && !sink) ||
+        n_vec < 0 || waves_per_cu < 0 || waves_per_cu > 32)
+        return EAGER_EINVAL;
+    if (read_half_mask && (n_vec & 1)) return EAGER_EINVAL;
+    if (n_read < 64 && (read_half_mask >> n_read)) return EAGER_EINVAL;
+    eager::MixArgs a;
+    std::memset(&a, 0, sizeof a);
+    for (int j = 0; j < n_read; ++j) {
+        if (!read[j] || !aligned16(read[j])) return EAGER_EINVAL;
+        a.src[j] = read[j];
+    }
+    for (int j = 0; j < n_write; ++j) {
+        if (!write[j] || !aligned16(write[j])) return EAGER_EINVAL;
+        a.dst[j] = write[j];
+    }
+    a.half = read_half_mask;
+    a.sink = sink;
+    a.n_read = n_read;
+    a.n_write = n_write;
+    a.nvec = n_vec;
+    return eager::launch_mix(a, waves_per_cu, static_cast<hipStream_t>(stream)) == hipSuccess
                ? EAGER_OK : EAGER_EDEVICE;
 }
 

@@ -2,8 +2,7 @@
 // rule alone on a receive buffer (plain, or with a layer-wise rate per bucket: norms pass, rate,
 // update pass), and what processes that lag by more than one round need - a late gradient
 // stashed into a send buffer, the update of several weight views from one read of the result, the
-// model average (paper Section 5, last paragraph) - plus two plain streaming kernels for
-// calibration.  All of them are HBM streams: a lane owns 4 consecutive elements, 64-thread
+// model average (paper Section 5, last paragraph).  All of them are HBM streams: a lane owns 4 consecutive elements, 64-thread
 // workgroups, nontemporal accesses, occupancy chosen for the bytes in flight.
 #include "eager_device.h"
 
@@ -448,25 +447,6 @@ __global__ __launch_bounds__(64) void lars_kernel(const SgdArgs a, const StatsAr
     }
 }
 
-__global__ __launch_bounds__(64) void copy_kernel(f32x4 *dst, const f32x4 *src, long long nvec)
-{
-    const long long stride = static_cast<long long>(gridDim.x) * blockDim.x;
-    for (long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec;
-         i += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
-}
-
-__global__ __launch_bounds__(256) void read_kernel(const f32x4 *src, long long nvec, float *sink)
-{
-    const long long stride = static_cast<long long>(gridDim.x) * blockDim.x;
-    f32x4 acc = (f32x4)(0.0f);
-    for (long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x; i < nvec;
-         i += stride)
-        acc = acc + __builtin_nontemporal_load(src + i);
-    const float t = acc.x + acc.y + acc.z + acc.w;
-    if (t == 123.456f) *sink = t;   // keeps the loads alive; practically never taken
-}
-
 // Resident wavefronts per CU of the weight-view kernels when the caller leaves it open: what
 // counts is the KiB of loads in flight per CU, about 38 for the update (1 + 2 per view loads
 // per lane, views in chunks of 8) and 32 for the average (one load per view, chunks of 16).
@@ -594,27 +574,6 @@ hipError_t launch_sgd_lars(const SgdArgs &a, const StatsArgs &st, bool fast, hip
         if (nt) hipLaunchKernelGGL((lars_kernel<false, true>), grid, block, 0, stream, a, st);
         else hipLaunchKernelGGL((lars_kernel<false, false>), grid, block, 0, stream, a, st);
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream)
-{
-    const long long nvec = nbytes / 16;
-    if (nvec <= 0) return hipSuccess;
-    // the fastest plain copy found on MI355X: 64-thread workgroups, one vector per lane
-    long long g = (nvec + 63) / 64;
-    if (g > kMaxGridThreads / 64) g = kMaxGridThreads / 64;   // the kernel strides
-    hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(g)), dim3(64), 0, stream,
-                       static_cast<f32x4 *>(dst), static_cast<const f32x4 *>(src), nvec);
-    return hipGetLastError();
-}
-
-hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream)
-{
-    const long long nvec = nbytes / 16;
-    if (nvec <= 0) return hipSuccess;
-    hipLaunchKernelGGL(read_kernel, dim3(grid_for(nvec, 256, 256 * 32)), dim3(256), 0, stream,
-                       static_cast<const f32x4 *>(src), nvec, sink);
     return hipGetLastError();
 }
 

@@ -210,4 +210,17 @@ hipError_t launch_table_fill(long long *table, const long long *start_end, int n
 hipError_t launch_copy(void *dst, const void *src, long long nbytes, hipStream_t stream);
 hipError_t launch_read(const void *src, long long nbytes, float *sink, hipStream_t stream);
 
+// A plain kernel with a round's mix of streams (calibration): n_read streams are summed per
+// lane-vector and the sum is written to n_write streams.
+constexpr int kMixMaxRead = 80, kMixMaxWrite = 80;
+struct MixArgs {
+    const void *src[kMixMaxRead];
+    void *dst[kMixMaxWrite];
+    unsigned long long half;     // bit j: read stream j holds 8 bytes per lane-vector, not 16
+    void *sink;                  // 4 writable bytes (only touched when nothing is written)
+    int n_read, n_write;
+    long long nvec;              // lane-vectors per stream
+};
+hipError_t launch_mix(const MixArgs &a, int waves_per_cu, hipStream_t stream);
+
 }  // namespace eager

@@ -4,7 +4,7 @@
 // HIP runtime calls the host side uses are replaced by recorders, so every launch the host
 // side would make is checked for its element range, masks and order, and nothing needs a
 // GPU.  Built and run by tests/test_host_library.py.
-#include "../../include/eager.h"
+#include "../../include/eager_tuning.h"
 #include "../../paper_1908_04207_amd/csrc/eager_internal.h"
 
 #include <cstdio>
@@ -104,6 +104,14 @@ hipError_t launch_table_fill(long long *table, const long long *start_end, int n
 }
 hipError_t launch_copy(void *, const void *, long long, hipStream_t) { return hipSuccess; }
 hipError_t launch_read(const void *, long long, float *, hipStream_t) { return hipSuccess; }
+hipError_t launch_mix(const MixArgs &a, int, hipStream_t)
+{
+    Launched l;
+    l.kind = "mix";
+    l.n = a.nvec; l.count = a.n_read; l.b_hi = a.n_write; l.active = a.half;
+    g_log.push_back(l);
+    return hipSuccess;
+}
 }  // namespace eager
 
 #define CHECK(cond)                                                              \
@@ -276,6 +284,24 @@ int main()
               EAGER_OK);
         CHECK(g_log.size() == 4 && g_log[0].count == EAGER_STATIC_MAX_BUCKETS);
         CHECK(eager_destroy(ctx) == EAGER_OK);
+    }
+
+    // the calibration kernel checks its stream tables before it launches
+    {
+        g_log.clear();
+        const void *rd[3] = {G[0], G[1], G[2]};
+        void *wr[2] = {R[0], R[1]};
+        CHECK(eager_calib_mix(rd, 3, 0b100, wr, 2, 1024, 4, nullptr, nullptr) == EAGER_OK);
+        CHECK(g_log.size() == 1 && g_log[0].kind == "mix" && g_log[0].count == 3 && g_log[0].b_hi == 2 &&
+              g_log[0].active == 0b100 && g_log[0].n == 1024);
+        CHECK(eager_calib_mix(rd, 3, 0b1000, wr, 2, 1024, 4, nullptr, nullptr) == EAGER_EINVAL);   // mask beyond n_read
+        CHECK(eager_calib_mix(rd, 3, 0b001, wr, 2, 1023, 4, nullptr, nullptr) == EAGER_EINVAL);    // odd with half-width
+        CHECK(eager_calib_mix(rd, 3, 0, wr, 0, 1024, 4, nullptr, nullptr) == EAGER_EINVAL);        // no sink
+        CHECK(eager_calib_mix(rd, 81, 0, wr, 2, 1024, 4, nullptr, nullptr) == EAGER_EINVAL);
+        CHECK(eager_calib_mix(rd, 3, 0, wr, 2, 1024, 33, nullptr, nullptr) == EAGER_EINVAL);
+        rd[1] = nullptr;
+        CHECK(eager_calib_mix(rd, 3, 0, wr, 2, 1024, 4, nullptr, nullptr) == EAGER_EINVAL);
+        CHECK(g_log.size() == 1);
     }
 
     // creation errors leave nothing behind

@@ -1,7 +1,8 @@
-/* The public header must be usable from plain C: this file includes it in a C99 translation
+/* The public headers must be usable from plain C: this file includes them in a C99 translation
  * unit, takes the address of every entry point with its declared type, and checks the layout
  * of the structures that cross the boundary.  Compiled (not run) by tests/test_host_library.py. */
 #include "eager.h"
+#include "eager_tuning.h"
 
 #include <stddef.h>
 
@@ -29,6 +30,9 @@ int (*const p_stash)(eager_ctx *, int, int, int, const void *, float *, void *) 
 int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
 int (*const p_lars)(eager_ctx *, int, int, const float *, const eager_opt *, float, float, void *) =
     eager_sgd_step_lars;
+int (*const p_lars_static)(eager_ctx *, int, int, const float *, const eager_opt *, float, float,
+                           eager_bucket_stats *, void *) = eager_sgd_step_lars_static;
+const char *(*const p_source_hash)(void) = eager_source_hash;
 int (*const p_views)(eager_ctx *, int, int, const float *, int, float *const *, float *const *, float,
                      float, void *) = eager_sgd_step_views;
 int (*const p_average)(eager_ctx *, int, int, int, float *const *, void *) = eager_average_views;
@@ -40,6 +44,8 @@ int (*const p_set_valid)(eager_ctx *, int, uint64_t) = eager_set_valid;
 int (*const p_set_launch)(eager_ctx *, const char *, int) = eager_set_launch;
 int (*const p_calib_copy)(void *, const void *, int64_t, void *) = eager_calib_copy;
 int (*const p_calib_read)(const void *, int64_t, float *, void *) = eager_calib_read;
+int (*const p_calib_mix)(const void *const *, int, uint64_t, void *const *, int, int64_t, int, float *,
+                         void *) = eager_calib_mix;
 
 /* host-only calls can run without a GPU: plan one round of each kind */
 int main(void)
