@@ -70,6 +70,9 @@ typedef struct {
     uint64_t mask;
     int32_t  initiator;   /* rank that triggered the round */
     int32_t  nap;         /* popcount(mask) >= 1 (Lemma 1, quorum size) */
+    uint32_t flags;       /* EAGER_FLAG_* the plan was made under (0 for a plan built by hand
+                             without such a promise) */
+    uint32_t reserved;    /* 0 */
 } eager_plan;
 
 /* Update rule U of Algorithm 2, lines 7-8: momentum SGD.  params/momentum are device
@@ -119,7 +122,10 @@ const char *eager_source_hash(void);
  * plus window_ms (Section 7.1; the window models the activation reaching processes that
  * arrive at a similar time, Section 4.2; use 0 for the paper's definition).  Ties count
  * as on time; a tie for first place goes to the lowest rank.
- * flags: EAGER_FLAG_STRICT_QUORUM (majority only) also waits for ceil(P/2) arrivals.
+ * flags: EAGER_FLAG_STRICT_QUORUM (majority only) also waits for ceil(P/2) arrivals, the
+ *        literal reading of "at least half of the processes" (Section 4.2, first paragraph);
+ *        the flag is recorded in out->flags, and eager_partial_allreduce_majority refuses a
+ *        plan that carries it with fewer than ceil(P/2) active processes.
  * Errors: EINVAL (NULL, P outside 1..64, unknown mode, NaN time, negative window).
  */
 int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t seed,
@@ -153,10 +159,15 @@ int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step
  *           only recv is produced (then recv must not be NULL)
  * On success the validity of every bucket in the range becomes ~mask (the late processes).
  * The three entry points run the same kernels and differ in what they accept:
- * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY, _quorum EAGER_QUORUM.
+ * _solo requires plan->mode == EAGER_SOLO, _majority EAGER_MAJORITY, _quorum EAGER_QUORUM;
+ * _majority also requires nap >= ceil(P/2) of a plan whose flags hold EAGER_FLAG_STRICT_QUORUM.
  * Errors: EINVAL (NULL, alignment, b0 >= b1, range), ESTATE (mode or P mismatch,
- * initiator not in mask, nap != popcount(mask), mask beyond P bits, bucket already
- * stepped with this plan->step), EDEVICE.  Non-finite gradients are not an error; they
+ * initiator not in mask, nap != popcount(mask), mask beyond P bits, unknown flag bits, a strict
+ * majority plan without its quorum, bucket already stepped with this plan->step), EDEVICE.
+ * Launch shapes are checked for every run of the call before the first kernel is enqueued, so
+ * EDEVICE can only come from the HIP runtime; after EDEVICE the buckets of the call are in an
+ * undefined state (some runs may have been enqueued): set their validity again with
+ * eager_set_valid before going on.  Non-finite gradients are not an error; they
  * propagate through the arithmetic.
  */
 int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
@@ -168,6 +179,29 @@ int eager_partial_allreduce_majority(eager_ctx *ctx, const eager_plan *plan, int
 int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                    const void *const *grads, float *const *resid,
                                    float *recv, const eager_opt *opt, void *stream);
+
+/*
+ * One round over the whole model in which the gradient a late process finishes becomes its send
+ * buffer WITHOUT being copied (Section 5: the late gradient is "stored in the send buffer" - here
+ * the buffer it was produced in simply takes that role).  For fp32 gradients only, where both
+ * buffers have the same layout.  The round reads the on-time gradients, the pending send buffers,
+ * w and v, and writes w and v: 4 * (active + pending) + 16 bytes per element instead of
+ * 4 * P + 4 * pending + 4 * late + 16.  Results (w, v, recv, and what every pending send buffer
+ * holds) are those of eager_partial_allreduce_* bit for bit.
+ *   grads, resid   host arrays of P device pointers as above, but the call MODIFIES them: for
+ *                  every late process p the two entries are exchanged - resid[p] then points to
+ *                  the buffer that holds the late gradient (pending, validity bit set) and
+ *                  grads[p] to the former send buffer, whose content has been delivered and which
+ *                  is free for the process's next gradient.  Entries of on-time processes stay.
+ *                  The caller must use the tables as they come back for every later call.
+ * Any plan mode is accepted; the range is always every bucket of the context (the exchange of a
+ * process's arena pointers concerns all of its buckets).
+ * Errors: as eager_partial_allreduce_*; ESTATE also for a context with bf16 gradients.  On an
+ * error the tables are unchanged.
+ */
+int eager_partial_allreduce_exchange(eager_ctx *ctx, const eager_plan *plan, const void **grads,
+                                     float **resid, float *recv, const eager_opt *opt,
+                                     void *stream);
 
 /*
  * Processes that lag by more than one round (Section 5, last paragraph).  The entry points

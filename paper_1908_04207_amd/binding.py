@@ -26,7 +26,7 @@ EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string", "eager_source_hash",
     "eager_plan_participation", "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_partial_allreduce_lagging", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
+    "eager_partial_allreduce_lagging", "eager_partial_allreduce_exchange", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
     "eager_sgd_step_lars_static", "eager_sgd_step_views",
     "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
@@ -44,7 +44,7 @@ class EagerError(RuntimeError):
 class Plan(ctypes.Structure):
     _fields_ = [("mode", ctypes.c_int32), ("P", ctypes.c_int32), ("step", ctypes.c_uint64),
                 ("mask", ctypes.c_uint64), ("initiator", ctypes.c_int32),
-                ("nap", ctypes.c_int32)]
+                ("nap", ctypes.c_int32), ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
     def __repr__(self):
         return (f"Plan(mode={self.mode}, P={self.P}, step={self.step}, mask={self.mask:#x}, "
@@ -89,6 +89,8 @@ def _load() -> ctypes.CDLL:
     lib.eager_partial_allreduce_lagging.argtypes = [
         vp, ctypes.POINTER(Plan), u64, i32, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
         ctypes.POINTER(Opt), vp]
+    lib.eager_partial_allreduce_exchange.argtypes = [
+        vp, ctypes.POINTER(Plan), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.POINTER(Opt), vp]
     lib.eager_stash.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
     lib.eager_sgd_step_lars.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), ctypes.c_float,
@@ -163,11 +165,12 @@ def eager_plan_quorum(arrival_ms: Sequence[float], quorum: int, step: int,
     return plan
 
 
-def make_plan(mode: int, P: int, step: int, mask: int, initiator: Optional[int] = None) -> Plan:
+def make_plan(mode: int, P: int, step: int, mask: int, initiator: Optional[int] = None,
+              flags: int = 0) -> Plan:
     """A plan the caller decides itself (tests, forced masks)."""
     if initiator is None:
         initiator = (mask & -mask).bit_length() - 1
-    return Plan(mode, P, step, mask, initiator, bin(mask).count("1"))
+    return Plan(mode, P, step, mask, initiator, bin(mask).count("1"), flags, 0)
 
 
 class Context:
@@ -241,6 +244,29 @@ class Context:
         fn = lambda h, pl, *rest: lib.eager_partial_allreduce_lagging(h, pl, absent, *rest)  # noqa: E731
         self._allreduce(fn, "eager_partial_allreduce_lagging", plan, grads, resid, recv, opt, b0,
                         b1, stream)
+
+    def eager_partial_allreduce_exchange(self, plan: Plan, grads, resid, recv=None, opt=None,
+                                         stream=None) -> None:
+        """`grads` and `resid` are pointer tables from Context.pointers (the library exchanges
+        the entries of late processes in them), or lists of device buffers - then the two lists
+        are permuted in place the way the library permuted their pointers."""
+        tables = isinstance(grads, ctypes.Array)
+        g = grads if tables else self.pointers(grads)
+        r = resid if tables else self.pointers(resid)
+        o = None
+        if opt is not None:
+            params, momentum, lr, mu = opt
+            o = ctypes.byref(Opt(_ptr(params), _ptr(momentum), lr, mu))
+        if len(grads) != self.P or len(resid) != self.P:
+            raise EagerError(EINVAL, f"eager_partial_allreduce_exchange: expected {self.P} "
+                                     "gradient and send buffers")
+        self._check(lib.eager_partial_allreduce_exchange(self._h, ctypes.byref(plan), g, r,
+                                                         _ptr(recv), o, _stream(stream)),
+                    "eager_partial_allreduce_exchange")
+        if not tables:
+            for p in range(self.P):
+                if g[p] != _ptr(grads[p]):          # exchanged by the library
+                    grads[p], resid[p] = resid[p], grads[p]
 
     def eager_stash(self, process: int, grad, resid, b0: int = 0, b1: Optional[int] = None,
                     stream=None) -> None:

@@ -135,9 +135,12 @@ int check_opt(eager_ctx *ctx, const eager_opt *opt)
 }
 
 // want_mode < 0: any mode.  absent: processes outside the mask that store no gradient.
+// exchange: the gradient buffer of a late process becomes its send buffer by an exchange of the
+// two pointers in the caller's tables (done by the caller of this function on success) instead
+// of a copy: the round then neither reads nor writes the late gradients.
 int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uint64_t absent,
                       int b0, int b1, const void *const *grads, float *const *resid,
-                      float *recv, const eager_opt *opt, void *stream)
+                      float *recv, const eager_opt *opt, void *stream, bool exchange = false)
 {
     if (!ctx) return EAGER_EINVAL;
     if (!plan || !grads || !resid) return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
@@ -162,6 +165,12 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         return fail(ctx, EAGER_ESTATE, "plan->nap %d is not popcount(mask) >= 1", plan->nap);
     if (plan->initiator < 0 || plan->initiator >= P || !((plan->mask >> plan->initiator) & 1ull))
         return fail(ctx, EAGER_ESTATE, "initiator %d is not in the mask", plan->initiator);
+    if (plan->flags & ~EAGER_FLAG_STRICT_QUORUM)
+        return fail(ctx, EAGER_ESTATE, "plan->flags %#x holds unknown bits", plan->flags);
+    if (want_mode == EAGER_MAJORITY && (plan->flags & EAGER_FLAG_STRICT_QUORUM) &&
+        plan->nap < (P + 1) / 2)
+        return fail(ctx, EAGER_ESTATE, "a strict majority round needs %d of %d processes, the plan has %d",
+                    (P + 1) / 2, P, plan->nap);
     for (int p = 0; p < P; ++p) {
         const bool needs_g = !((absent >> p) & 1ull);       // an absent process has no gradient
         if ((needs_g && !grads[p]) || !resid[p])
@@ -198,6 +207,20 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         stats_layout(ctx, ctx->workspace, ctx->stats, a.stats);
     }
 
+    // Everything that could make a launcher refuse is checked for every run before the first
+    // kernel is enqueued (the launch keys are validated when they are set): a run longer than
+    // one grid covers.  After this point only the HIP runtime can fail.
+    for (int b = b0; b < b1;) {
+        int e = b + 1;
+        while (e < b1 && ctx->valid[e] == ctx->valid[b]) ++e;
+        const int64_t n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
+        if (n > (int64_t{1} << 33))
+            return fail(ctx, EAGER_EINVAL, "buckets %d..%d span %lld elements in one send-buffer state; "
+                                           "one call covers at most 2^33 per such stretch: use smaller ranges",
+                        b, e - 1, static_cast<long long>(n));
+        b = e;
+    }
+
     // Consecutive buckets whose send buffers are in the same state form one run = one
     // launch over a contiguous element range (after a whole-model round every bucket is
     // in the same state, so a round is normally a single launch however small the
@@ -210,7 +233,8 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         a.e0 = ctx->offset[b];
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
         const uint64_t late = ~plan->mask & ~absent & low_bits(P);   // finish a gradient late
-        const bool split = use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
+        const bool split = exchange ||
+                           use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
         a.gload = split ? plan->mask : (plan->mask | late);
         a.store = split ? 0 : late;
         if (round_stats) {
@@ -231,7 +255,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
                 return fail(ctx, EAGER_EDEVICE, "statistics kernel launch failed: %s",
                             hipGetErrorString(he));
         }
-        if (split) {
+        if (split && !exchange) {
             // same stream: the reduction has read every pending R_p before it is overwritten
             eager::CarryArgs c;
             std::memset(&c, 0, sizeof c);
@@ -339,6 +363,7 @@ int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t
     if (P < 1 || P > EAGER_MAX_P) return EAGER_EINVAL;
     if (mode != EAGER_SOLO && mode != EAGER_MAJORITY) return EAGER_EINVAL;
     if (!(window_ms >= 0.0)) return EAGER_EINVAL;
+    if (flags & ~EAGER_FLAG_STRICT_QUORUM) return EAGER_EINVAL;
     for (int p = 0; p < P; ++p)
         if (std::isnan(arrival_ms[p])) return EAGER_EINVAL;
 
@@ -372,6 +397,8 @@ int eager_plan_participation(int mode, int P, const double *arrival_ms, uint64_t
     out->mask = mask;
     out->initiator = init;
     out->nap = popcount64(mask);
+    out->flags = mode == EAGER_MAJORITY ? (flags & EAGER_FLAG_STRICT_QUORUM) : 0u;
+    out->reserved = 0u;
     return EAGER_OK;
 }
 
@@ -401,6 +428,8 @@ int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step
     out->mask = mask;
     out->initiator = init;
     out->nap = popcount64(mask);
+    out->flags = 0u;
+    out->reserved = 0u;
     return EAGER_OK;
 }
 
@@ -431,6 +460,26 @@ int eager_partial_allreduce_lagging(eager_ctx *ctx, const eager_plan *plan, uint
                                     void *stream)
 {
     return partial_allreduce(ctx, -1, plan, absent, b0, b1, grads, resid, recv, opt, stream);
+}
+
+int eager_partial_allreduce_exchange(eager_ctx *ctx, const eager_plan *plan, const void **grads,
+                                     float **resid, float *recv, const eager_opt *opt, void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    if (ctx->bf16)
+        return fail(ctx, EAGER_ESTATE, "a gradient buffer can only become a send buffer when both "
+                                       "hold fp32 (this context has bf16 gradients)");
+    const int st = partial_allreduce(ctx, -1, plan, 0, 0, ctx->n_buckets, grads, resid, recv, opt,
+                                     stream, true);
+    if (st != EAGER_OK) return st;
+    const uint64_t late = ~plan->mask & low_bits(ctx->P);
+    for (int p = 0; p < ctx->P; ++p)
+        if ((late >> p) & 1ull) {
+            float *pending = const_cast<float *>(static_cast<const float *>(grads[p]));
+            grads[p] = resid[p];
+            resid[p] = pending;
+        }
+    return EAGER_OK;
 }
 
 int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,

@@ -21,6 +21,7 @@ struct Launched {
     bool has_w = false, has_recv = false, has_stats = false;
 };
 static std::vector<Launched> g_log;
+static int g_fail_round = -1;       // the round launch with this index in g_log reports a failure
 
 extern "C" hipError_t hipMemcpyAsync(void *, const void *, size_t, hipMemcpyKind, hipStream_t)
 {
@@ -38,6 +39,7 @@ hipError_t launch_round(const RoundArgs &a, bool, bool, const Launch &, hipStrea
     l.kind = "round";
     l.e0 = a.e0; l.n = a.n; l.active = a.active; l.valid = a.valid; l.gload = a.gload; l.store = a.store;
     l.has_w = a.w != nullptr; l.has_recv = a.recv != nullptr; l.has_stats = a.stats.stats != nullptr;
+    if (static_cast<int>(g_log.size()) == g_fail_round) return hipErrorLaunchFailure;
     g_log.push_back(l);
     return hipSuccess;
 }
@@ -127,6 +129,8 @@ static eager_plan plan_of(int mode, int P, uint64_t step, uint64_t mask, int ini
     eager_plan p;
     p.mode = mode; p.P = P; p.step = step; p.mask = mask; p.initiator = initiator;
     p.nap = __builtin_popcountll(mask);
+    p.flags = 0;
+    p.reserved = 0;
     return p;
 }
 
@@ -160,6 +164,24 @@ int main()
     CHECK(eager_partial_allreduce_solo(ctx, &p0, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_ESTATE);
     CHECK(g_log.size() == 1 && std::string(eager_last_error(ctx)).find("already") != std::string::npos);
 
+    // a majority plan made under the strict reading needs its quorum at the entry point too
+    {
+        eager_plan strict = plan_of(EAGER_MAJORITY, P, 77, 0b0001, 0);
+        strict.flags = EAGER_FLAG_STRICT_QUORUM;
+        CHECK(eager_partial_allreduce_majority(ctx, &strict, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_ESTATE);
+        CHECK(std::string(eager_last_error(ctx)).find("strict majority") != std::string::npos);
+        strict.flags = 2u;
+        CHECK(eager_partial_allreduce_majority(ctx, &strict, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_ESTATE);
+        CHECK(g_log.size() == 1);
+        const double t4[4] = {4.0, 1.0, 3.0, 2.0};
+        eager_plan made;
+        CHECK(eager_plan_participation(EAGER_MAJORITY, P, t4, 5u, 0u, 0.0, EAGER_FLAG_STRICT_QUORUM, &made) == EAGER_OK);
+        CHECK(made.flags == EAGER_FLAG_STRICT_QUORUM && made.nap >= 2 && made.reserved == 0);
+        CHECK(eager_plan_participation(EAGER_SOLO, P, t4, 5u, 0u, 0.0, EAGER_FLAG_STRICT_QUORUM, &made) == EAGER_OK);
+        CHECK(made.flags == 0);
+        CHECK(eager_plan_participation(EAGER_MAJORITY, P, t4, 5u, 0u, 0.0, 4u, &made) == EAGER_EINVAL);
+    }
+
     // buckets in different send-buffer states: one launch per run of equal state
     g_log.clear();
     CHECK(eager_set_valid(ctx, 1, 0b0100) == EAGER_OK);
@@ -171,6 +193,24 @@ int main()
     CHECK(g_log[2].e0 == 16 && g_log[2].n == whole - 16 && g_log[2].valid == 0b1100 && g_log[2].store == 0 &&
           g_log[2].has_recv);
     for (int b = 0; b < NB; ++b) CHECK(eager_get_valid(ctx, b, &valid) == EAGER_OK && valid == 0);
+
+    // a launch that the runtime refuses in the middle of a call: EDEVICE; the runs enqueued before
+    // it stay stepped (documented: the range is in an undefined state), and setting the validity
+    // again makes the buckets usable
+    {
+        g_log.clear();
+        CHECK(eager_set_valid(ctx, 1, 0b0100) == EAGER_OK);
+        g_fail_round = 1;
+        eager_plan pf = plan_of(EAGER_SOLO, P, 40, 0b0001, 0);
+        CHECK(eager_partial_allreduce_solo(ctx, &pf, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_EDEVICE);
+        g_fail_round = -1;
+        CHECK(g_log.size() == 1 && g_log[0].e0 == 0 && g_log[0].n == 5);
+        CHECK(std::string(eager_last_error(ctx)).find("launch failed") != std::string::npos);
+        CHECK(eager_partial_allreduce_solo(ctx, &pf, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_ESTATE);
+        for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, 0) == EAGER_OK);
+        CHECK(eager_partial_allreduce_solo(ctx, &pf, 0, NB, G, R, nullptr, &opt, nullptr) == EAGER_OK);
+        for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, 0) == EAGER_OK);
+    }
 
     // the split form: the reduction reads only the on-time gradients, a copy kernel follows
     g_log.clear();
@@ -192,6 +232,28 @@ int main()
     CHECK(g_log.size() == 1 && g_log[0].store == 0b0101 && g_log[0].gload == 0b0111 && g_log[0].valid == 0b1001);
     CHECK(eager_get_valid(ctx, 1, &valid) == EAGER_OK && valid == 0b0101);
     CHECK(eager_partial_allreduce_lagging(ctx, &p3, 0b0010, 0, 1, G, R, nullptr, &opt, nullptr) == EAGER_ESTATE);
+
+    // the gradient buffer of a late process becomes its send buffer: the reduction alone (it reads
+    // only the on-time gradients), no copy kernel, the two table entries exchanged
+    {
+        g_log.clear();
+        const void *Gx[P] = {G[0], G[1], G[2], G[3]};
+        float *Rx[P] = {R[0], R[1], R[2], R[3]};
+        uint64_t before[NB];
+        for (int b = 0; b < NB; ++b) CHECK(eager_get_valid(ctx, b, &before[b]) == EAGER_OK);
+        eager_plan px = plan_of(EAGER_MAJORITY, P, 30, 0b0101, 2);
+        CHECK(eager_partial_allreduce_exchange(ctx, &px, Gx, Rx, nullptr, &opt, nullptr) == EAGER_OK);
+        for (const Launched &l : g_log) CHECK(l.kind == "round" && l.gload == 0b0101 && l.store == 0);
+        CHECK(!g_log.empty() && g_log.front().e0 == 0 && g_log.back().e0 + g_log.back().n == whole);
+        CHECK(Gx[0] == G[0] && Rx[0] == R[0] && Gx[2] == G[2] && Rx[2] == R[2]);
+        CHECK(Gx[1] == R[1] && Rx[1] == G[1] && Gx[3] == R[3] && Rx[3] == G[3]);
+        for (int b = 0; b < NB; ++b) CHECK(eager_get_valid(ctx, b, &valid) == EAGER_OK && valid == 0b1010);
+        // refused calls leave the tables alone
+        CHECK(eager_partial_allreduce_exchange(ctx, &px, Gx, Rx, nullptr, &opt, nullptr) == EAGER_ESTATE);
+        CHECK(Gx[1] == R[1] && Rx[1] == G[1]);
+        // back to the state the following checks expect
+        for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, before[b]) == EAGER_OK);
+    }
 
     // a stash runs per stretch of buckets in which the process's buffer is in the same state
     g_log.clear();

@@ -6,7 +6,8 @@
 
 #include <stddef.h>
 
-typedef char static_check_plan[(sizeof(eager_plan) == 32 && offsetof(eager_plan, mask) == 16) ? 1 : -1];
+typedef char static_check_plan[(sizeof(eager_plan) == 40 && offsetof(eager_plan, mask) == 16 &&
+                                offsetof(eager_plan, flags) == 32) ? 1 : -1];
 typedef char static_check_stats[(sizeof(eager_bucket_stats) == 32 &&
                                  offsetof(eager_bucket_stats, rate) == 24) ? 1 : -1];
 typedef char static_check_opt[(offsetof(eager_opt, lr) == 2 * sizeof(void *)) ? 1 : -1];
@@ -26,6 +27,8 @@ int (*const p_quorum)(eager_ctx *, const eager_plan *, int, int, const void *con
                       float *, const eager_opt *, void *) = eager_partial_allreduce_quorum;
 int (*const p_lagging)(eager_ctx *, const eager_plan *, uint64_t, int, int, const void *const *,
                        float *const *, float *, const eager_opt *, void *) = eager_partial_allreduce_lagging;
+int (*const p_exchange)(eager_ctx *, const eager_plan *, const void **, float **, float *, const eager_opt *,
+                        void *) = eager_partial_allreduce_exchange;
 int (*const p_stash)(eager_ctx *, int, int, int, const void *, float *, void *) = eager_stash;
 int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
 int (*const p_lars)(eager_ctx *, int, int, const float *, const eager_opt *, float, float, void *) =

@@ -79,24 +79,32 @@ def test_full_size_sampled(eb, k, steps, order, launch):
 
     w0 = wg.values_at(S_t, cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma).numpy()
     oracle = eo.OracleState(cfg.P, [0], [len(S)], len(S), w0, cfg.lr, cfg.mu)
+    # the last round also fills the receive buffer (the other rounds run without one, as the
+    # benchmark does)
+    recv = torch.empty(n, device=dev)
+    oracle_recv = np.zeros(len(S), dtype=np.float32)
 
     for t in range(steps):
         print(f"{cfg.name} order={order} step {t}", flush=True)
         plan = plan_for(eb, cfg, t)
         for p in range(cfg.P):
             wg.fill(G[p], cfg.seed, t, p, cfg.grad_sigma)
-        ctx.eager_partial_allreduce(plan, G, R, opt=(w, v, cfg.lr, cfg.mu))
+        last = t == steps - 1
+        ctx.eager_partial_allreduce(plan, G, R, recv=recv if last else None,
+                                    opt=(w, v, cfg.lr, cfg.mu))
         Gs = [as_oracle_grad(wg.grad_at(S_t, cfg.seed, t, p, cfg.grad_sigma, gdt))
               for p in range(cfg.P)]
         # the generator gives the same bits on both devices
         assert np.array_equal(as_oracle_grad(G[t % cfg.P][S_dev]), Gs[t % cfg.P])
-        oracle.round(plan.mask, Gs)
+        oracle.round(plan.mask, Gs, recv=oracle_recv if last else None)
         torch.cuda.synchronize()
         valid = ctx.eager_get_valid(0)
         assert all(ctx.eager_get_valid(b) == valid for b in range(bt.n_buckets))
         assert valid == oracle.valid[0]
         got = {"w": w[S_dev].cpu().numpy(), "v": v[S_dev].cpu().numpy()}
         want = {"w": oracle.w, "v": oracle.v}
+        if last:
+            got["recv"], want["recv"] = recv[S_dev].cpu().numpy(), oracle_recv
         for p in range(cfg.P):
             if (valid >> p) & 1:
                 got[f"R{p}"] = R[p][S_dev].cpu().numpy()
@@ -107,8 +115,8 @@ def test_full_size_sampled(eb, k, steps, order, launch):
                     f"{cfg.name} step {t}: {name} differs at " \
                     f"{int(np.sum(bits(got[name]) != bits(want[name])))} of {len(S)} samples"
             else:
-                tol = 1e-2 if cfg.grad_dtype == "bf16" else 1e-6
-                assert normwise(got[name], want[name]) <= tol, (cfg.name, t, name)
+                # 1e-6 also with bf16 gradients (stated bound 1e-2): widening is exact
+                assert normwise(got[name], want[name]) <= 1e-6, (cfg.name, t, name)
     ctx.close()
 
 

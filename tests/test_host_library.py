@@ -53,6 +53,53 @@ def test_plan_matches_oracle_on_all_configs():
                    (lm, cfg.P, step, b.mask, b.initiator, b.nap)
 
 
+def test_designated_initiator_is_the_published_splitmix64_sequence():
+    """The shared-seed draw of the majority initiator (Section 4.2) against the published
+    SplitMix64 outputs for seed 0: the residues of a 64-bit value modulo every P in 1..64
+    determine it (their least common multiple exceeds 2^64), so this pins the library's and the
+    oracle's generator completely through the planner alone."""
+    path = os.path.join(ROOT, "tests", "golden", "splitmix64_seed0.txt")
+    published = [int(l, 16) for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(published) == 3
+    for step, value in enumerate(published):
+        for P in range(1, 65):
+            times_ = [float(p) for p in range(P)]
+            assert eb.eager_plan_participation(eb.MAJORITY, times_, 0, step).initiator == value % P
+            assert eo.plan_participation(eo.MAJORITY, P, times_, 0, step).initiator == value % P
+
+
+def test_strict_quorum_is_enforced_where_the_round_is_entered():
+    """Majority as "at least half of the processes" (Section 4.2, first paragraph): the planner
+    records the flag in the plan and eager_partial_allreduce_majority refuses such a plan with
+    fewer than ceil(P/2) active processes before anything is launched."""
+    P = 5
+    c = eb.Context(P, [0], [64])
+    ptrs = [0x10000 * (p + 1) for p in range(P)]
+    opt = (0x900000, 0xA00000, 0.1, 0.9)
+    plan = eb.eager_plan_participation(eb.MAJORITY, [5.0, 1.0, 4.0, 2.0, 3.0], 3, 0, 0.0,
+                                       eb.FLAG_STRICT_QUORUM)
+    assert plan.flags == eb.FLAG_STRICT_QUORUM and plan.nap >= 3
+    assert eb.eager_plan_participation(eb.MAJORITY, [5.0, 1.0, 4.0, 2.0, 3.0], 3, 0).flags == 0
+    for nap_mask, ok in ((0b00011, False), (0b00111, True)):
+        forged = eb.make_plan(eb.MAJORITY, P, 9, nap_mask, flags=eb.FLAG_STRICT_QUORUM)
+        if ok:
+            continue                                   # would launch: covered on the GPU
+        with pytest.raises(eb.EagerError) as err:
+            c.eager_partial_allreduce_majority(forged, ptrs, ptrs, opt=opt, stream=0)
+        assert err.value.status == eb.ESTATE and "strict majority" in str(err.value)
+    # without the flag the same participation set is accepted by the checks (a plan built by hand
+    # promises nothing): it fails later, on purpose, with a NULL gradient pointer instead
+    with pytest.raises(eb.EagerError) as err:
+        c.eager_partial_allreduce_majority(eb.make_plan(eb.MAJORITY, P, 9, 0b00011),
+                                           [0] * P, ptrs, opt=opt, stream=0)
+    assert err.value.status == eb.EINVAL
+    with pytest.raises(eb.EagerError) as err:                      # unknown flag bits
+        c.eager_partial_allreduce_majority(eb.make_plan(eb.MAJORITY, P, 9, 0b00111, flags=8), ptrs, ptrs,
+                                           opt=opt, stream=0)
+    assert err.value.status == eb.ESTATE
+    c.close()
+
+
 def test_plan_matches_oracle_random_with_ties_window_and_strict_quorum():
     rng = np.random.default_rng(0)
     for it in range(2000):

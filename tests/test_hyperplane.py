@@ -99,16 +99,24 @@ def test_lagging_processes_drift_apart_and_synchronisation_repairs_it(hp):
     assert 3.6 < loss_solo_sync < 6.0                  # noise floor 4.0
 
 
-def test_time_model_reproduces_the_reported_speedups():
+def test_time_model_is_the_closed_form_it_claims():
+    """The simulated clock, not the paper's measurement: with a base time b, a seeded jitter
+    and ONE of the 8 ranks delayed by d per step, a synchronous round lasts about b + d and a
+    solo round about b, so the modelled speedup is (b + d) / b.  The default b = 400 ms was
+    CHOSEN so that this gives the paper's 1.50x / 1.75x / 2.01x for 200 / 300 / 400 ms (Section
+    7.2); the test pins the closed form of the model, and that the stored paper values are what
+    b was fitted to - it reproduces no measurement."""
     from harness import paper_values
     from paper_1908_04207_amd import hyperplane as hp
     pv = paper_values()
     assert pv["hyperplane_processes"] == 8 and pv["hyperplane_parameters"] == 8192 + 1
-    for delay in (200.0, 300.0, 400.0):
-        reported = pv[f"hyperplane_speedup_{int(delay)}ms"]
-        t_sync = t_solo = 0.0
-        for t in range(2000):
-            arr = hp.arrival_times(8, 7, t, 400.0, delay)
-            t_sync += max(arr)
-            t_solo += min(arr)
-        assert abs(t_sync / t_solo - reported) < 0.03, (delay, t_sync / t_solo)
+    for base in (250.0, 400.0, 1000.0):
+        for delay in (200.0, 300.0, 400.0):
+            t_sync = t_solo = 0.0
+            for t in range(2000):
+                arr = hp.arrival_times(8, 7, t, base, delay)
+                t_sync += max(arr)
+                t_solo += min(arr)
+            assert abs(t_sync / t_solo - (base + delay) / base) < 0.03, (base, delay)
+            if base == 400.0:       # what the default was fitted to
+                assert abs((base + delay) / base - pv[f"hyperplane_speedup_{int(delay)}ms"]) < 0.02
