@@ -145,6 +145,26 @@ int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step
                       double window_ms, eager_plan *out);
 
 /*
+ * Processes that keep their own clock (Section 5, last paragraph): the k-th call of a process
+ * belongs to the k-th execution of the collective, and the processes whose call has reached the
+ * execution that is open wait at it.  eager_plan_open_round decides, from who is waiting, whether
+ * execution `round` is triggered now:
+ *   EAGER_SOLO      (Section 4.1) as soon as anybody waits; the initiator is the lowest waiting
+ *                   rank (several wait only if they arrived at the same instant)
+ *   EAGER_MAJORITY  (Section 4.2) when the designated initiator of this round - the rank all
+ *                   processes draw from the shared seed, eager_designated_initiator - waits
+ *   EAGER_QUORUM    (Section 9) when `quorum` (1..P) processes wait; the initiator is `newest`
+ * waiting: bit p = process p waits (not empty); newest: the rank among them that arrived last.
+ * *triggered becomes 1 or 0; when 1, *out is the plan of the execution: the waiting processes
+ * are the active ones (they arrived no later than the initiator, Section 7.1), step = round.
+ * Host only, pure.  Errors: EINVAL (NULL, P outside 1..64, unknown mode, empty or out-of-range
+ * waiting set, newest not waiting, quorum outside 1..P in quorum mode).
+ */
+int eager_designated_initiator(uint64_t seed, uint64_t round, int P, int *rank);
+int eager_plan_open_round(int mode, int P, uint64_t waiting, int newest, int quorum,
+                          uint64_t seed, uint64_t round, int *triggered, eager_plan *out);
+
+/*
  * One round of the partial allreduce over buckets [b0, b1) (Section 5; Algorithm 2
  * line 6), optionally fused with the update rule (lines 7-8).
  *   plan    host; produced by eager_plan_participation or built by the caller

@@ -25,8 +25,9 @@ rounds executed so far r):
 Every `sync_every` rounds the models are synchronised: every w_p and v_p is replaced by the
 average over the processes (the periodic model synchronisation that Section 5 prescribes).
 
-All arithmetic runs in the library: the round (`eager_partial_allreduce_lagging`, receive
-buffer only), the update rule on the weight views of the processes that see a result
+Whether the open round executes, and its plan, is decided by the library
+(`eager_plan_open_round`), and all arithmetic runs there: the round
+(`eager_partial_allreduce_lagging`, receive buffer only), the update rule on the weight views of the processes that see a result
 (`eager_sgd_step_views`, one kernel), the stash (`eager_stash`) and the model average
 (`eager_average_views`).  This module is the event loop and the bookkeeping.
 
@@ -79,19 +80,6 @@ class AsyncEagerSGD:
         self.track_divergence = track_divergence
         self.res = AsyncResult(calls=[0] * P, late_calls=[0] * P, missed=[0] * P)
 
-    def _designated(self) -> int:
-        """The designated initiator of the open round, as eager_plan_participation draws it."""
-        return eb.eager_plan_participation(eb.MAJORITY, [0.0] * self.P, self.seed, self.r).initiator
-
-    def _triggered(self) -> bool:
-        if self.mode == "solo":
-            return True
-        if self.mode == "majority":
-            return self._designated() in self.waiting
-        if self.mode == "quorum":
-            return len(self.waiting) >= self.quorum
-        raise ValueError(self.mode)
-
     def _apply(self, procs: Sequence[int]) -> None:
         """The listed processes apply the result in the receive buffer (the latest round's)
         to their own weights: one kernel, one read of the result."""
@@ -131,15 +119,16 @@ class AsyncEagerSGD:
                 self.held[p] = gradient(p, self.k[p], self.w[p])
                 self.waiting.append(p)
                 self.res.calls[p] += 1
-            if not any(p in self.waiting for p in arrived) or not self._triggered():
+            if not any(p in self.waiting for p in arrived):
                 continue
+            # whether the open execution is triggered, and its plan, is the library's decision
             mask = sum(1 << p for p in self.waiting)
-            absent = ((1 << P) - 1) & ~mask
             mode = {"solo": eb.SOLO, "majority": eb.MAJORITY, "quorum": eb.QUORUM}[self.mode]
-            initiator = {"solo": self.waiting[0], "quorum": self.waiting[-1]}.get(self.mode)
-            if initiator is None:
-                initiator = self._designated()
-            plan = eb.make_plan(mode, P, self.r, mask, initiator=initiator)
+            plan = eb.eager_plan_open_round(mode, P, mask, self.waiting[-1], self.r, self.quorum,
+                                            self.seed)
+            if plan is None:
+                continue
+            absent = ((1 << P) - 1) & ~mask
             grads = [self.held.get(p) for p in range(P)]
             self.ctx.eager_partial_allreduce_lagging(plan, absent, grads, self.R, recv=self.recv)
             self.r += 1

@@ -24,7 +24,8 @@ MAX_P = 64
 
 EXPORTS = (
     "eager_create", "eager_destroy", "eager_last_error", "eager_status_string", "eager_source_hash",
-    "eager_plan_participation", "eager_partial_allreduce_solo",
+    "eager_plan_participation", "eager_designated_initiator", "eager_plan_open_round",
+    "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
     "eager_partial_allreduce_lagging", "eager_partial_allreduce_exchange", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
     "eager_sgd_step_lars_static", "eager_sgd_step_views",
@@ -80,6 +81,9 @@ def _load() -> ctypes.CDLL:
     lib.eager_plan_participation.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), u64, u64,
                                              ctypes.c_double, ctypes.c_uint32,
                                              ctypes.POINTER(Plan)]
+    lib.eager_designated_initiator.argtypes = [u64, u64, i32, ctypes.POINTER(i32)]
+    lib.eager_plan_open_round.argtypes = [i32, i32, u64, i32, i32, u64, u64, ctypes.POINTER(i32),
+                                          ctypes.POINTER(Plan)]
     lib.eager_plan_quorum.argtypes = [i32, ctypes.POINTER(ctypes.c_double), i32, u64,
                                       ctypes.c_double, ctypes.POINTER(Plan)]
     for f in (lib.eager_partial_allreduce_solo, lib.eager_partial_allreduce_majority,
@@ -163,6 +167,25 @@ def eager_plan_quorum(arrival_ms: Sequence[float], quorum: int, step: int,
     if st != OK:
         raise EagerError(st, f"eager_plan_quorum: {status_string(st)}")
     return plan
+
+
+def eager_designated_initiator(seed: int, round_: int, P: int) -> int:
+    rank = ctypes.c_int()
+    st = lib.eager_designated_initiator(seed & (2 ** 64 - 1), round_, P, ctypes.byref(rank))
+    if st != OK:
+        raise EagerError(st, f"eager_designated_initiator: {status_string(st)}")
+    return rank.value
+
+
+def eager_plan_open_round(mode: int, P: int, waiting: int, newest: int, round_: int,
+                          quorum: int = 0, seed: int = 0) -> Optional[Plan]:
+    """The plan of execution `round_` if the waiting processes trigger it, else None."""
+    go, plan = ctypes.c_int(), Plan()
+    st = lib.eager_plan_open_round(mode, P, waiting, newest, quorum, seed & (2 ** 64 - 1), round_,
+                                   ctypes.byref(go), ctypes.byref(plan))
+    if st != OK:
+        raise EagerError(st, f"eager_plan_open_round: {status_string(st)}")
+    return plan if go.value else None
 
 
 def make_plan(mode: int, P: int, step: int, mask: int, initiator: Optional[int] = None,

@@ -433,6 +433,47 @@ int eager_plan_quorum(int P, const double *arrival_ms, int quorum, uint64_t step
     return EAGER_OK;
 }
 
+int eager_designated_initiator(uint64_t seed, uint64_t round, int P, int *rank)
+{
+    if (!rank || P < 1 || P > EAGER_MAX_P) return EAGER_EINVAL;
+    *rank = static_cast<int>(initiator_hash(seed, round) % static_cast<uint64_t>(P));
+    return EAGER_OK;
+}
+
+int eager_plan_open_round(int mode, int P, uint64_t waiting, int newest, int quorum,
+                          uint64_t seed, uint64_t round, int *triggered, eager_plan *out)
+{
+    if (!triggered || !out || P < 1 || P > EAGER_MAX_P) return EAGER_EINVAL;
+    if (mode < EAGER_SOLO || mode > EAGER_QUORUM) return EAGER_EINVAL;
+    if (waiting == 0 || (waiting & ~low_bits(P))) return EAGER_EINVAL;
+    if (newest < 0 || newest >= P || !((waiting >> newest) & 1ull)) return EAGER_EINVAL;
+    if (mode == EAGER_QUORUM && (quorum < 1 || quorum > P)) return EAGER_EINVAL;
+    int init = 0;
+    bool go = false;
+    if (mode == EAGER_SOLO) {
+        go = true;
+        init = __builtin_ctzll(waiting);
+    } else if (mode == EAGER_MAJORITY) {
+        init = static_cast<int>(initiator_hash(seed, round) % static_cast<uint64_t>(P));
+        go = (waiting >> init) & 1ull;
+    } else {
+        go = popcount64(waiting) >= quorum;
+        init = newest;
+    }
+    *triggered = go ? 1 : 0;
+    if (go) {
+        out->mode = mode;
+        out->P = P;
+        out->step = round;
+        out->mask = waiting;
+        out->initiator = init;
+        out->nap = popcount64(waiting);
+        out->flags = 0u;
+        out->reserved = 0u;
+    }
+    return EAGER_OK;
+}
+
 int eager_partial_allreduce_solo(eager_ctx *ctx, const eager_plan *plan, int b0, int b1,
                                  const void *const *grads, float *const *resid, float *recv,
                                  const eager_opt *opt, void *stream)

@@ -19,6 +19,9 @@ const char *(*const p_status_string)(int) = eager_status_string;
 int (*const p_plan)(int, int, const double *, uint64_t, uint64_t, double, uint32_t, eager_plan *) =
     eager_plan_participation;
 int (*const p_plan_quorum)(int, const double *, int, uint64_t, double, eager_plan *) = eager_plan_quorum;
+int (*const p_designated)(uint64_t, uint64_t, int, int *) = eager_designated_initiator;
+int (*const p_open_round)(int, int, uint64_t, int, int, uint64_t, uint64_t, int *, eager_plan *) =
+    eager_plan_open_round;
 int (*const p_solo)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
                     float *, const eager_opt *, void *) = eager_partial_allreduce_solo;
 int (*const p_majority)(eager_ctx *, const eager_plan *, int, int, const void *const *, float *const *,
@@ -60,5 +63,15 @@ int main(void)
     if (eager_plan_quorum(4, arrival, 3, 0u, 0.0, &plan) != EAGER_OK) return 3;
     if (plan.initiator != 2 || plan.mask != 0xEu || plan.mode != EAGER_QUORUM) return 4;
     if (eager_plan_quorum(4, arrival, 5, 0u, 0.0, &plan) != EAGER_EINVAL) return 5;
+    {
+        int go = -1, rank = -1;
+        if (eager_designated_initiator(0u, 0u, 64, &rank) != EAGER_OK || rank != 0x2F) return 6;
+        if (eager_plan_open_round(EAGER_QUORUM, 4, 0x6u, 2, 3, 0u, 7u, &go, &plan) != EAGER_OK || go != 0) return 7;
+        if (eager_plan_open_round(EAGER_QUORUM, 4, 0x7u, 0, 3, 0u, 7u, &go, &plan) != EAGER_OK || go != 1) return 8;
+        if (plan.initiator != 0 || plan.mask != 0x7u || plan.nap != 3 || plan.step != 7u) return 9;
+        if (eager_plan_open_round(EAGER_SOLO, 4, 0xCu, 3, 0, 0u, 1u, &go, &plan) != EAGER_OK || !go ||
+            plan.initiator != 2) return 10;
+        if (eager_plan_open_round(EAGER_SOLO, 4, 0x0u, 0, 0, 0u, 1u, &go, &plan) != EAGER_EINVAL) return 11;
+    }
     return 0;
 }

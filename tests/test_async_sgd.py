@@ -3,7 +3,8 @@ paragraph): processes that lag by more than one round, stale gradients that accu
 send buffer, results missed in the receive buffer, diverging weights, periodic model
 synchronisation.
 
-The CPU tests pin the oracle's event loop against what the paper and arithmetic fix; the GPU
+The CPU tests pin the oracle (a closed-form timetable, a ledger of deliveries, an arithmetic walk)
+against what the paper and arithmetic fix and against a tick-by-tick brute force; the GPU
 tests run the library-driven loop (all arithmetic in the kernels) and the oracle's,
 independently, on the same seeded compute times and gradients and compare every state bit
 for bit.
@@ -144,46 +145,172 @@ def test_what_triggers_a_round():
     assert full["time_ms"] > maj["time_ms"] > 0
 
 
+def _tick_schedule(P, mode, rounds, ms, quorum=0, seed=0):
+    """The rules of the model written out tick by tick, for compute times that are whole
+    numbers (no arithmetic, no closed form): at every tick, the processes whose gradient is
+    done make their call - those whose execution is already over are late (by rank) and start
+    their next gradient at once, the others wait at the open execution - and then the
+    execution runs if its trigger condition holds.  Returns per execution (tick, active set)
+    and per gradient (process, call) the execution that delivers it (None: still in a send
+    buffer)."""
+    done_at = [ms(p, 0) for p in range(P)]           # tick at which the current gradient is done
+    call = [0] * P
+    waiting, pending = [], [[] for _ in range(P)]
+    executed, log, delivered = 0, [], {}
+    tick = 0
+    while executed < rounds:
+        tick += 1
+        assert tick < 10_000
+        for p in range(P):
+            if p not in waiting and done_at[p] == tick and call[p] < executed:
+                pending[p].append((p, call[p]))
+                delivered[(p, call[p])] = None
+                call[p] += 1
+                done_at[p] = tick + ms(p, call[p])
+        for p in range(P):
+            if p not in waiting and done_at[p] == tick and call[p] == executed:
+                waiting.append(p)
+        if not waiting:
+            continue
+        if mode == "solo":
+            go = True
+        elif mode == "majority":
+            go = eo.initiator_hash(seed, executed) % P in waiting
+        else:
+            go = len(waiting) >= quorum
+        if not go:
+            continue
+        for p in range(P):
+            for c in pending[p]:
+                delivered[c] = executed
+            pending[p] = []
+        for p in waiting:
+            delivered[(p, call[p])] = executed
+            call[p] += 1
+            done_at[p] = tick + ms(p, call[p])
+        log.append((tick, sum(1 << p for p in waiting)))
+        waiting = []
+        executed += 1
+    return log, delivered
+
+
+def test_timetable_and_ledger_against_the_rules_tick_by_tick():
+    """Brute force over EVERY table of whole-number compute times (1..3 ticks, so ties of every
+    kind occur; two values where three would take minutes) for up to 3 processes and 4 calls, in
+    every mode: the oracle's closed-form timetable and its ledger of deliveries equal a
+    tick-by-tick walk through the rules."""
+    import itertools
+    checked = 0
+    for P, rounds, ticks in ((1, 3, (1, 2, 3)), (2, 4, (1, 2, 3)), (3, 2, (1, 2, 3)), (3, 3, (1, 2)),
+                             (3, 4, (1, 3))):
+        cells = P * (rounds + 1)
+        for table in itertools.product(ticks, repeat=cells):
+            ms = lambda p, k, t=table, r=rounds: t[p * (r + 1) + k]      # noqa: E731
+            modes = [("solo", {}), ("majority", {"seed": 1}), ("majority", {"seed": 6})]
+            modes += [("quorum", {"quorum": q}) for q in range(1, P + 1)]
+            for mode, kw in modes:
+                arrive, trigger, active = ao.timetable(P, mode, rounds, ms, **kw)
+                want_log, want_delivery = _tick_schedule(P, mode, rounds, ms, **kw)
+                got_log = [(trigger[k], sum(1 << p for p in range(P) if active[p][k]))
+                           for k in range(rounds)]
+                assert got_log == [(float(t), m) for t, m in want_log], (table, mode, kw)
+                assert ao.ledger(P, rounds, arrive, trigger, active) == want_delivery, (table, mode, kw)
+                checked += 1
+    assert checked > 400_000
+
+
+@pytest.mark.parametrize("mode,kw", [("solo", {}), ("majority", {"seed": 3}), ("quorum", {"quorum": 2})])
+def test_every_result_holds_exactly_the_gradients_the_ledger_names(mode, kw):
+    """Gradient (p, k) is a distinct power of two in every element, P = 4, lr = 1, mu = 0: all
+    sums are exact, so each result, times P, spells out which gradients it delivered, and each
+    weight view which results its process read.  Both must be what the ledger and the rules
+    say - for the arithmetic walk of the oracle this is an end-to-end check that does not rest
+    on the oracle's round routine."""
+    P, n, T = 4, 3, 5
+
+    def ms(p, k):
+        return [2.0, 3.0, 1.0, 7.0, 2.0, 11.0, 1.0][(p * 3 + k * 2) % 7]
+    out = ao.simulate(P, n, np.zeros(n, np.float32), 1.0, 0.0, mode, T, ms,
+                      lambda p, k, w: np.full(n, 2.0 ** (p * (T + 1) + k), np.float32),
+                      keep_results=True, **kw)
+    assert any(v is not None and v != c[1] for c, v in out["ledger"].items())     # somebody was late
+    for r, u in enumerate(out["results"]):
+        code = int(u[0] * P)
+        assert float(code) == float(u[0]) * P and np.all(u == u[0])
+        named = {c for c, v in out["ledger"].items() if v == r}
+        assert code == sum(1 << (p * (T + 1) + k) for p, k in named), (r, named)
+    for p in range(P):
+        code = int(out["send"][p][0]) if out["has_stale"][p] else 0
+        assert code == sum(1 << (q * (T + 1) + k) for (q, k), v in out["ledger"].items()
+                           if v is None and q == p)
+        read = sum(float(out["results"][r][0]) for r in out["applied"][p])
+        assert float(-out["w"][p][0]) == read
+
+
 ASYNC_MUTATIONS = {
     "a late gradient overwrites a pending one":
-        ("eo.stash_f32(g, send[p], has_stale[p])", "eo.stash_f32(g, send[p], False)"),
+        ("eo.stash_f32(gradient(p, k, w[p]), send[p], bool(in_send[p]))",
+         "eo.stash_f32(gradient(p, k, w[p]), send[p], False)"),
     "the latest result is applied again":
         ("if last_applied[p] < executed - 1:", "if executed > 0:"),
     "majority does not wait for its initiator":
-        ("fire = eo.initiator_hash(seed, executed) % P in blocked", "fire = True"),
+        ("fired = at[eo.initiator_hash(seed, k) % P]", "fired = min(at)"),
     "quorum waits for one process too many":
-        ("fire = len(blocked) >= quorum", "fire = len(blocked) > quorum"),
+        ("fired = sorted(at)[quorum - 1]", "fired = sorted(at)[min(quorum, P - 1)]"),
     "processes that are still computing are treated as late":
-        ("absent=everyone & ~active)", "absent=0)"),
+        ("absent=everyone & ~mask)", "absent=0)"),
     "send buffers are not emptied by a round":
-        ("        has_stale = [False] * P\n        executed += 1", "        executed += 1"),
+        ("            in_send = [[] for _ in range(P)]\n            if keep_results:", "            if keep_results:"),
     "an active process does not read the result":
-        ("        for p in blocked:\n            read_receive_buffer(p)\n", "        for p in blocked:\n"),
+        ("            for q in sorted(fresh):\n                read_receive_buffer(q, k)\n", ""),
+    "a tie with the initiator counts as late":
+        ("on_time = at[p] <= fired", "on_time = at[p] < fired or at[p] == min(at)"),
+    "an active process does not wait for the execution to be over":
+        ("arrive[p].append((fired if on_time else at[p]) +", "arrive[p].append(at[p] +"),
+    "a gradient that comes with the trigger is delivered one execution later":
+        ("if trigger[j] >= arrive[p][k]]", "if trigger[j] > arrive[p][k]]"),
 }
 
 
 @pytest.mark.parametrize("name", list(ASYNC_MUTATIONS))
 def test_a_planted_mistake_in_the_loop_fails_a_pin(name, monkeypatch):
-    """The pins above bite: each mistake planted in a copy of the oracle's event loop makes
-    one of them fail (on the CPU; the GPU path is not involved)."""
+    """The pins above bite: each mistake planted in a copy of the oracle's module makes one of
+    them fail (on the CPU; the GPU path is not involved)."""
     import inspect
     old, new = ASYNC_MUTATIONS[name]
-    src = inspect.getsource(ao.simulate)
+    src = inspect.getsource(ao)
     assert src.count(old) == 1, f"mutation site not unique: {old!r}"
-    scope = dict(vars(ao))
+    scope = {"__name__": ao.__name__, "__package__": ao.__package__}
     exec(compile(src.replace(old, new), "<mutant>", "exec"), scope)
-    monkeypatch.setattr(ao, "simulate", scope["simulate"])
+    for fn in ("timetable", "ledger", "simulate"):
+        monkeypatch.setattr(ao, fn, scope[fn])
     caught = False
     for pin in (test_equal_compute_times_are_synchronous_sgd, test_what_triggers_a_round,
                 lambda: test_every_gradient_is_delivered_exactly_once("solo", {}),
                 lambda: test_every_gradient_is_delivered_exactly_once("majority", {"seed": 5}),
-                lambda: test_every_gradient_is_delivered_exactly_once("quorum", {"quorum": 2})):
+                lambda: test_every_gradient_is_delivered_exactly_once("quorum", {"quorum": 2}),
+                lambda: test_every_result_holds_exactly_the_gradients_the_ledger_names("solo", {}),
+                lambda: test_every_result_holds_exactly_the_gradients_the_ledger_names("quorum", {"quorum": 2}),
+                _small_tick_check):
         try:
             pin()
         except (AssertionError, ValueError, IndexError, KeyError):
             caught = True
             break
     assert caught, f"no pin noticed: {name}"
+
+
+def _small_tick_check():
+    """A slice of the tick-by-tick brute force (two processes, three calls), for the mutants."""
+    import itertools
+    for table in itertools.product((1, 2, 3), repeat=8):
+        ms = lambda p, k, t=table: t[p * 4 + k]                          # noqa: E731
+        for mode, kw in (("solo", {}), ("majority", {"seed": 1}), ("quorum", {"quorum": 2})):
+            arrive, trigger, active = ao.timetable(2, mode, 3, ms, **kw)
+            want_log, want_delivery = _tick_schedule(2, mode, 3, ms, **kw)
+            assert [(trigger[k], sum(1 << p for p in range(2) if active[p][k])) for k in range(3)] == \
+                [(float(t), m) for t, m in want_log]
+            assert ao.ledger(2, 3, arrive, trigger, active) == want_delivery
 
 
 # ------------------------------------------------------------------ GPU: library loop == oracle loop

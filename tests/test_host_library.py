@@ -68,6 +68,41 @@ def test_designated_initiator_is_the_published_splitmix64_sequence():
             assert eo.plan_participation(eo.MAJORITY, P, times_, 0, step).initiator == value % P
 
 
+def test_open_round_trigger_rule():
+    """eager_plan_open_round (processes with their own clocks, Section 5 last paragraph): solo
+    triggers as soon as anybody waits, majority when the designated initiator waits, quorum q at
+    q waiting processes; the plan's active set is the waiting set."""
+    rng = np.random.default_rng(5)
+    for it in range(3000):
+        P = int(rng.integers(1, 65))
+        waiting = 0
+        while waiting == 0:
+            waiting = int(rng.integers(0, 2 ** 62)) & ((1 << P) - 1) if P < 62 else \
+                int(rng.integers(0, 2 ** 62)) | (1 << (P - 1))
+        members = [p for p in range(P) if (waiting >> p) & 1]
+        newest = int(rng.choice(members))
+        seed, rnd = int(rng.integers(0, 2 ** 63)), int(rng.integers(0, 1000))
+        designated = eo.initiator_hash(seed, rnd) % P
+        assert eb.eager_designated_initiator(seed, rnd, P) == designated
+        solo = eb.eager_plan_open_round(eb.SOLO, P, waiting, newest, rnd)
+        assert solo is not None and (solo.mask, solo.initiator, solo.nap, solo.step, solo.mode) == \
+            (waiting, members[0], len(members), rnd, eb.SOLO)
+        maj = eb.eager_plan_open_round(eb.MAJORITY, P, waiting, newest, rnd, seed=seed)
+        assert (maj is not None) == (designated in members)
+        if maj is not None:
+            assert (maj.mask, maj.initiator, maj.nap) == (waiting, designated, len(members))
+        q = int(rng.integers(1, P + 1))
+        quo = eb.eager_plan_open_round(eb.QUORUM, P, waiting, newest, rnd, quorum=q)
+        assert (quo is not None) == (len(members) >= q)
+        if quo is not None:
+            assert (quo.mask, quo.initiator, quo.mode) == (waiting, newest, eb.QUORUM)
+    for bad in (dict(waiting=0, newest=0), dict(waiting=0b10000, newest=4), dict(waiting=0b0011, newest=2)):
+        with pytest.raises(eb.EagerError):
+            eb.eager_plan_open_round(eb.SOLO, 4, bad["waiting"], bad["newest"], 0)
+    with pytest.raises(eb.EagerError):
+        eb.eager_plan_open_round(eb.QUORUM, 4, 0b0011, 1, 0, quorum=5)
+
+
 def test_strict_quorum_is_enforced_where_the_round_is_entered():
     """Majority as "at least half of the processes" (Section 4.2, first paragraph): the planner
     records the flag in the plan and eager_partial_allreduce_majority refuses such a plan with
