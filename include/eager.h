@@ -245,6 +245,19 @@ int eager_partial_allreduce_lagging(eager_ctx *ctx, const eager_plan *plan, uint
 int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,
                 void *stream);
 
+/*
+ * The round in which nobody hands over a gradient (what is left in the send buffers when
+ * training ends; Section 6.1: every update is applied once, now or later): every pending send
+ * buffer of buckets [b0, b1) is delivered - u = (sum of the pending R_p, ascending rank, from
+ * +0.0f) / P goes to recv and, with opt, through the update rule like any other round's result
+ * (u = 0 where nothing was pending: the momentum still acts) - and all send buffers of the range
+ * are empty afterwards.  It has no initiator and no round index (a plan cannot express it:
+ * Lemma 1 wants at least one active process), so it may follow any round.
+ * Errors: EINVAL (NULL resid, alignment, range, recv and opt both NULL), EDEVICE.
+ */
+int eager_flush(eager_ctx *ctx, int b0, int b1, float *const *resid, float *recv,
+                const eager_opt *opt, void *stream);
+
 /* The update rule alone (Algorithm 2, lines 7-8) on buckets [b0, b1): reads u from
  * `update` (device fp32 arena, e.g. a receive buffer), updates opt->params/momentum.
  * Errors: EINVAL, EDEVICE. */
@@ -308,8 +321,9 @@ typedef struct {
  *              allocated while attached, and is shared by all calls of this context: with
  *              statistics attached, the calls of a context must be ordered (one stream, or
  *              events), and no other context may use the same workspace concurrently
- *   stream     the bucket table is uploaded on this stream (asynchronously; rounds that
- *              use the statistics must be ordered after it, e.g. on the same stream)
+ *   stream     the bucket table is written into the workspace by a small kernel on this stream
+ *              (rounds that use the statistics must be ordered after it, e.g. on the same
+ *              stream)
  * Needs the compact path with its default chunk size ("compact" = 1, "chunk" = 0 or 16);
  * otherwise the next round fails with ESTATE.  One extra small kernel runs per launch.
  * Errors: EINVAL (NULL ctx, workspace too small or misaligned), ENOMEM, EDEVICE.

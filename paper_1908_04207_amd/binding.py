@@ -27,7 +27,8 @@ EXPORTS = (
     "eager_plan_participation", "eager_designated_initiator", "eager_plan_open_round",
     "eager_partial_allreduce_solo",
     "eager_partial_allreduce_majority", "eager_partial_allreduce_quorum", "eager_plan_quorum",
-    "eager_partial_allreduce_lagging", "eager_partial_allreduce_exchange", "eager_stash", "eager_sgd_step", "eager_sgd_step_lars",
+    "eager_partial_allreduce_lagging", "eager_partial_allreduce_exchange", "eager_stash",
+    "eager_flush", "eager_sgd_step", "eager_sgd_step_lars",
     "eager_sgd_step_lars_static", "eager_sgd_step_views",
     "eager_average_views", "eager_set_update_rule", "eager_stats_workspace_bytes",
     "eager_stats_attach", "eager_get_valid",
@@ -96,6 +97,7 @@ def _load() -> ctypes.CDLL:
     lib.eager_partial_allreduce_exchange.argtypes = [
         vp, ctypes.POINTER(Plan), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.POINTER(Opt), vp]
     lib.eager_stash.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.eager_flush.argtypes = [vp, i32, i32, ctypes.POINTER(vp), vp, ctypes.POINTER(Opt), vp]
     lib.eager_sgd_step.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), vp]
     lib.eager_sgd_step_lars.argtypes = [vp, i32, i32, vp, ctypes.POINTER(Opt), ctypes.c_float,
                                         ctypes.c_float, vp]
@@ -296,6 +298,17 @@ class Context:
         b1 = self.n_buckets if b1 is None else b1
         self._check(lib.eager_stash(self._h, process, b0, b1, _ptr(grad), _ptr(resid),
                                     _stream(stream)), "eager_stash")
+
+    def eager_flush(self, resid, recv=None, opt=None, b0: int = 0, b1: Optional[int] = None,
+                    stream=None) -> None:
+        b1 = self.n_buckets if b1 is None else b1
+        r = resid if isinstance(resid, ctypes.Array) else self.pointers(resid)
+        o = None
+        if opt is not None:
+            params, momentum, lr, mu = opt
+            o = ctypes.byref(Opt(_ptr(params), _ptr(momentum), lr, mu))
+        self._check(lib.eager_flush(self._h, b0, b1, r, _ptr(recv), o, _stream(stream)),
+                    "eager_flush")
 
     def eager_partial_allreduce(self, plan: Plan, *a, **kw):
         """Dispatch on plan.mode to the entry point of that name."""

@@ -140,10 +140,14 @@ int check_opt(eager_ctx *ctx, const eager_opt *opt)
 // of a copy: the round then neither reads nor writes the late gradients.
 int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uint64_t absent,
                       int b0, int b1, const void *const *grads, float *const *resid,
-                      float *recv, const eager_opt *opt, void *stream, bool exchange = false)
+                      float *recv, const eager_opt *opt, void *stream, bool exchange = false,
+                      bool flush = false)
 {
+    // flush: the round in which nobody hands over a gradient (every process absent, nobody
+    // active): `plan` is a stand-in without an initiator and belongs to no round index
     if (!ctx) return EAGER_EINVAL;
-    if (!plan || !grads || !resid) return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
+    if (!plan || (!grads && !flush) || !resid)
+        return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
     if (int st = check_range(ctx, b0, b1)) return st;
     if (!opt && !recv)
         return fail(ctx, EAGER_EINVAL, "nothing to produce: recv and opt are both NULL");
@@ -161,9 +165,10 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
     if (absent & ~low_bits(P)) return fail(ctx, EAGER_ESTATE, "absent mask has bits beyond P");
     if (plan->P != P) return fail(ctx, EAGER_ESTATE, "plan->P %d != context P %d", plan->P, P);
     if (plan->mask & ~low_bits(P)) return fail(ctx, EAGER_ESTATE, "plan->mask has bits beyond P");
-    if (plan->nap != popcount64(plan->mask) || plan->nap < 1)
+    if (plan->nap != popcount64(plan->mask) || (plan->nap < 1 && !flush))
         return fail(ctx, EAGER_ESTATE, "plan->nap %d is not popcount(mask) >= 1", plan->nap);
-    if (plan->initiator < 0 || plan->initiator >= P || !((plan->mask >> plan->initiator) & 1ull))
+    if (!flush &&
+        (plan->initiator < 0 || plan->initiator >= P || !((plan->mask >> plan->initiator) & 1ull)))
         return fail(ctx, EAGER_ESTATE, "initiator %d is not in the mask", plan->initiator);
     if (plan->flags & ~EAGER_FLAG_STRICT_QUORUM)
         return fail(ctx, EAGER_ESTATE, "plan->flags %#x holds unknown bits", plan->flags);
@@ -178,7 +183,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         if ((needs_g && !aligned16(grads[p])) || !aligned16(resid[p]))
             return fail(ctx, EAGER_EINVAL, "grads[%d] / resid[%d] must be 16-byte aligned", p, p);
     }
-    for (int b = b0; b < b1; ++b)
+    for (int b = b0; b < b1 && !flush; ++b)
         if (ctx->stepped[b] && ctx->last_step[b] == plan->step)
             return fail(ctx, EAGER_ESTATE, "bucket %d was already stepped with round %llu", b,
                         static_cast<unsigned long long>(plan->step));
@@ -186,7 +191,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
     eager::RoundArgs a;
     std::memset(&a, 0, sizeof a);
     for (int p = 0; p < P; ++p) {
-        a.g[p] = grads[p];
+        a.g[p] = grads ? grads[p] : nullptr;
         a.r[p] = resid[p];
     }
     a.active = plan->mask;
@@ -275,7 +280,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         for (int k = b; k < e; ++k) {
             ctx->valid[k] = late;
             ctx->last_step[k] = plan->step;
-            ctx->stepped[k] = 1;
+            ctx->stepped[k] = flush ? 0 : 1;
         }
         b = e;
     }
@@ -521,6 +526,18 @@ int eager_partial_allreduce_exchange(eager_ctx *ctx, const eager_plan *plan, con
             resid[p] = pending;
         }
     return EAGER_OK;
+}
+
+int eager_flush(eager_ctx *ctx, int b0, int b1, float *const *resid, float *recv,
+                const eager_opt *opt, void *stream)
+{
+    if (!ctx) return EAGER_EINVAL;
+    eager_plan nobody;
+    std::memset(&nobody, 0, sizeof nobody);
+    nobody.mode = EAGER_SOLO;
+    nobody.P = ctx->P;
+    return partial_allreduce(ctx, -1, &nobody, low_bits(ctx->P), b0, b1, nullptr, resid, recv, opt,
+                             stream, false, true);
 }
 
 int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,
@@ -786,11 +803,12 @@ int eager_stats_attach(eager_ctx *ctx, eager_bucket_stats *stats, void *workspac
                     static_cast<long long>(need));
     if (!aligned16(stats) || !aligned16(workspace))
         return fail(ctx, EAGER_EINVAL, "stats and workspace must be 16-byte aligned");
-    // the table lives in the context, so it outlives the copy
-    hipError_t he = hipMemcpyAsync(workspace, ctx->table.data(), ctx->table.size() * 8,
-                                   hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+    // written by a small kernel from the kernel arguments: no host-to-device copy, so the call
+    // can be captured in a graph like every other
+    hipError_t he = eager::launch_table_fill(static_cast<long long *>(workspace), ctx->table.data(),
+                                             ctx->n_buckets, static_cast<hipStream_t>(stream));
     if (he != hipSuccess)
-        return fail(ctx, EAGER_EDEVICE, "upload of the bucket table failed: %s", hipGetErrorString(he));
+        return fail(ctx, EAGER_EDEVICE, "writing the bucket table failed: %s", hipGetErrorString(he));
     ctx->stats = reinterpret_cast<eager::BucketStats *>(stats);
     ctx->workspace = static_cast<char *>(workspace);
     return EAGER_OK;

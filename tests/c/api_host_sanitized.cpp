@@ -1,7 +1,7 @@
 // The host side of the library (eager_api.cpp: context state, validation, how a bucket range
 // is cut into runs = launches, which form a round takes) compiled WITHOUT the kernels and run
-// under AddressSanitizer and UndefinedBehaviorSanitizer on the CPU.  The launchers and the two
-// HIP runtime calls the host side uses are replaced by recorders, so every launch the host
+// under AddressSanitizer and UndefinedBehaviorSanitizer on the CPU.  The launchers and the one
+// HIP runtime call the host side uses are replaced by recorders, so every launch the host
 // side would make is checked for its element range, masks and order, and nothing needs a
 // GPU.  Built and run by tests/test_host_library.py.
 #include "../../include/eager_tuning.h"
@@ -23,13 +23,6 @@ struct Launched {
 static std::vector<Launched> g_log;
 static int g_fail_round = -1;       // the round launch with this index in g_log reports a failure
 
-extern "C" hipError_t hipMemcpyAsync(void *, const void *, size_t, hipMemcpyKind, hipStream_t)
-{
-    Launched l;
-    l.kind = "upload";
-    g_log.push_back(l);
-    return hipSuccess;
-}
 extern "C" const char *hipGetErrorString(hipError_t) { return "stub"; }
 
 namespace eager {
@@ -255,6 +248,22 @@ int main()
         for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, before[b]) == EAGER_OK);
     }
 
+    // the flush: nobody active, everybody absent, no gradient table; validity cleared, and the
+    // same round index may be used again afterwards
+    {
+        g_log.clear();
+        uint64_t before[NB];
+        for (int b = 0; b < NB; ++b) CHECK(eager_get_valid(ctx, b, &before[b]) == EAGER_OK);
+        CHECK(eager_flush(ctx, 1, 3, R, recv, &opt, nullptr) == EAGER_OK);
+        for (const Launched &l : g_log) CHECK(l.kind == "round" && l.active == 0 && l.gload == 0 && l.store == 0);
+        CHECK(!g_log.empty() && g_log.front().e0 == 8 && g_log.back().e0 + g_log.back().n == 1016);
+        CHECK(eager_get_valid(ctx, 1, &valid) == EAGER_OK && valid == 0);
+        CHECK(eager_get_valid(ctx, 0, &valid) == EAGER_OK && valid == before[0]);
+        CHECK(eager_flush(ctx, 1, 3, R, nullptr, nullptr, nullptr) == EAGER_EINVAL);
+        CHECK(eager_flush(ctx, 1, 3, nullptr, recv, &opt, nullptr) == EAGER_EINVAL);
+        for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, before[b]) == EAGER_OK);
+    }
+
     // a stash runs per stretch of buckets in which the process's buffer is in the same state
     g_log.clear();
     CHECK(eager_stash(ctx, 0, 0, NB, G[0], R[0], nullptr) == EAGER_OK);     // bit 0: 0, 1, 1, 0
@@ -287,7 +296,7 @@ int main()
     CHECK(eager_sgd_step_lars(ctx, 0, NB, recv, &opt, 0.02f, 0.0f, nullptr) == EAGER_ESTATE);
     CHECK(eager_stats_attach(ctx, stats, ws, need - 1, nullptr) == EAGER_EINVAL);
     CHECK(eager_stats_attach(ctx, stats, ws, need, nullptr) == EAGER_OK);
-    CHECK(g_log.size() == 1 && g_log[0].kind == "upload");
+    CHECK(g_log.size() == 1 && g_log[0].kind == "table" && g_log[0].count == NB && !g_log[0].has_w);
     g_log.clear();
     for (int b = 0; b < NB; ++b) CHECK(eager_set_valid(ctx, b, 0) == EAGER_OK);
     eager_plan p4 = plan_of(EAGER_SOLO, P, 4, 0b1111, 0);

@@ -33,6 +33,7 @@ int (*const p_lagging)(eager_ctx *, const eager_plan *, uint64_t, int, int, cons
 int (*const p_exchange)(eager_ctx *, const eager_plan *, const void **, float **, float *, const eager_opt *,
                         void *) = eager_partial_allreduce_exchange;
 int (*const p_stash)(eager_ctx *, int, int, int, const void *, float *, void *) = eager_stash;
+int (*const p_flush)(eager_ctx *, int, int, float *const *, float *, const eager_opt *, void *) = eager_flush;
 int (*const p_sgd)(eager_ctx *, int, int, const float *, const eager_opt *, void *) = eager_sgd_step;
 int (*const p_lars)(eager_ctx *, int, int, const float *, const eager_opt *, float, float, void *) =
     eager_sgd_step_lars;

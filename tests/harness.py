@@ -123,6 +123,15 @@ class Pair:
         self.oracle.round(plan.mask, G_host, recv=self.oracle_recv if recv is not None else None,
                           fused=fused)
 
+    def flush(self, b0: int = 0, b1: Optional[int] = None, fused: bool = True) -> None:
+        """The round in which nobody hands over a gradient: pending send buffers delivered."""
+        opt = (self.w, self.v, self.lr, self.mu) if fused else None
+        self.ctx.eager_flush(self.R, recv=self.recv, opt=opt, b0=b0, b1=b1)
+        everyone = (1 << self.P) - 1
+        none = [np.zeros(self.arena, dtype=np.uint16 if self.dtype == torch.bfloat16 else np.float32)
+                for _ in range(self.P)]
+        self.oracle.round(0, none, b0, b1, recv=self.oracle_recv, fused=fused, absent=everyone)
+
     def stash(self, p: int, g: torch.Tensor, b0: int = 0, b1: Optional[int] = None) -> None:
         """A gradient of process p finished between two rounds (tensor on the host)."""
         dev = g.to(self.G[p].device)

@@ -777,6 +777,34 @@ def test_signed_zeros_bit_for_bit(eb, dtype, launch):
     assert np.signbit(pair.oracle_recv[pair.oracle_recv == 0.0]).sum() == 0
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_flush_delivers_what_is_pending(eb, dtype):
+    """eager_flush after rounds that left gradients in send buffers: bit for bit the oracle's
+    round with nobody active and everybody absent, on a bucket range first (the rest keeps its
+    pending buffers), then on everything; a second flush finds nothing and only lets the
+    momentum act.  With integer-valued gradients the whole run conserves them exactly."""
+    cfg = shapes.scaled(shapes.config(5 if dtype == "bf16" else 3), 3001)
+    bt = cfg.buckets
+    nb = bt.n_buckets
+    pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, seed=31)
+    for t in range(3):
+        pair.round(plan_for(eb, cfg, t), pair.fresh_grads(t))
+    assert pair.ctx.eager_get_valid(0) != 0
+    pair.flush(1, nb - 1)
+    pair.compare(exact=True, check_recv=True, b0=1, b1=nb - 1, what="flush of a range")
+    assert pair.ctx.eager_get_valid(0) != 0 and pair.ctx.eager_get_valid(1) == 0
+    pair.flush(fused=False)
+    pair.sgd()
+    pair.compare(exact=True, check_recv=True, what="flush of everything, unfused")
+    assert all(pair.ctx.eager_get_valid(b) == 0 for b in range(nb))
+    pair.flush()
+    pair.compare(exact=True, check_recv=True, what="flush with nothing pending")
+    assert float(pair.recv[bt.offset[0]:bt.offset[0] + bt.numel[0]].abs().max()) == 0.0
+    # a round may follow a flush with any index, also the last one used
+    pair.round(plan_for(eb, cfg, 2), pair.fresh_grads(2))
+    pair.compare(exact=True, what="round after a flush")
+
+
 def test_strict_majority_round(eb):
     """A majority round planned under the literal reading (at least half of the processes):
     the planner's participation set equals the oracle's, the entry point accepts it, and the

@@ -342,7 +342,7 @@ def test_other_entry_points_validate_on_the_host():
 
 
 def test_host_side_under_address_and_ub_sanitizers(tmp_path):
-    """eager_api.cpp compiled without the kernels (the launchers and the two runtime calls it
+    """eager_api.cpp compiled without the kernels (the launchers and the one runtime call it
     uses are recorders in tests/c/api_host_sanitized.cpp) and driven on the CPU under
     AddressSanitizer and UndefinedBehaviorSanitizer: how a bucket range is cut into launches,
     the fused and the split form, absent processes, stash runs, views, statistics and the
