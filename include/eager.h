@@ -317,15 +317,16 @@ typedef struct {
  *   stats      device array of n_buckets entries, 16-byte aligned, caller-owned; NULL detaches
  *   workspace  device memory, 16-byte aligned, caller-owned, at least
  *              eager_stats_workspace_bytes() bytes; the library keeps the bucket table, one
- *              32-byte record per wavefront of the round kernel and 129 per bucket there.  It must stay
- *              allocated while attached, and is shared by all calls of this context: with
+ *              32-byte record per wavefront of the round kernel and 129 per bucket there.  It
+ *              must stay allocated while attached, and is shared by all calls of this context: with
  *              statistics attached, the calls of a context must be ordered (one stream, or
  *              events), and no other context may use the same workspace concurrently
  *   stream     the bucket table is written into the workspace by a small kernel on this stream
  *              (rounds that use the statistics must be ordered after it, e.g. on the same
  *              stream)
- * Needs the compact path with its default chunk size ("compact" = 1, "chunk" = 0 or 16);
- * otherwise the next round fails with ESTATE.  One extra small kernel runs per launch.
+ * Needs the default number of streams in flight per wavefront (launch key "chunk" of
+ * eager_tuning.h at 0 or 16); otherwise the next round fails with ESTATE.  One extra small
+ * kernel runs per launch.
  * Errors: EINVAL (NULL ctx, workspace too small or misaligned), ENOMEM, EDEVICE.
  */
 int eager_stats_workspace_bytes(const eager_ctx *ctx, int64_t *bytes);
