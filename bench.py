@@ -539,7 +539,20 @@ def record_traffic(spec: str) -> int:
         total = 0.0
         for tag in ("slot_kernel", "carry_kernel"):
             total += sum(f.get(tag, [])) * fs * 1024 + sum(w.get(tag, [])) * ws * 1024
+        # algorithmic bytes of the same rounds (0 .. rounds-1 of the configuration)
+        from paper_1908_04207_amd import binding as eb
+        from workloads import times
+        g = 2 if cfg.grad_dtype == "bf16" else 4
+        q_prev, alg = 0, 0
+        for t in range(rounds):
+            plan = eb.eager_plan_participation(eb.SOLO if cfg.mode == "solo" else eb.MAJORITY,
+                                               times.compute_times(cfg.times, cfg.P, cfg.seed, t),
+                                               cfg.seed, t)
+            alg += alg_bytes_per_element(cfg.P, g, q_prev, cfg.P - plan.nap) * cfg.numel
+            q_prev = cfg.P - plan.nap
         rec["configs"][cfg.name] = {"bytes_per_round": round(total / rounds), "rounds": rounds,
+                                    "algorithmic_bytes_per_round_same_rounds": round(alg / rounds),
+                                    "over_algorithmic": round(total / alg, 4),
                                     "fetch_scale": round(fs, 4), "write_scale": round(ws, 4)}
     with open(TRAFFIC_FILE, "w") as fh:
         json.dump(rec, fh, indent=1)
@@ -660,7 +673,10 @@ def main() -> int:
                                       "by a copy kernel of known size); includes what the last-level "
                                       "cache serves, so an upper bound on HBM bytes") if traffic else None,
                      "traffic_source": ("bench_traffic.json, taken with the library whose source digest "
-                                        "matches the one loaded now") if traffic else None,
+                                        "matches the one loaded now, on rounds 0..%d of the configuration, whose "
+                                        "algorithmic bytes are %d per round: ratio %.4f" %
+                                        (traffic["rounds"] - 1, traffic["algorithmic_bytes_per_round_same_rounds"],
+                                         traffic["over_algorithmic"])) if traffic else None,
                      "kernel": head["kernels_per_round"],
                      "avg_kernel_ms": head["avg_kernel_ms_per_step"]},
         "per_config": per_config,
