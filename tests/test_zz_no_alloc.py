@@ -97,3 +97,64 @@ def test_static_scratch_alone_in_a_fresh_state():
         assert abs(raw[4 * b] - want) <= 1e-10 * max(want, 1e-300)
         assert raw.view(np.uint64)[4 * b + 2] == int((~fin).sum())
     assert rates.shape == (3,)
+
+
+def test_static_scratch_call_captured_in_a_graph():
+    """What the entry point is for: under HIP graph capture nothing may allocate, copy from
+    pageable memory or synchronise.  After one eager call (it looks up the array's address and
+    loads the kernels) the call is captured - together with an eager_stats_attach, whose bucket
+    table is written by a kernel - and replayed on new updates with eager work and
+    synchronisations in between; every replay must leave the bits of the same calls made eagerly
+    on a second copy of the state."""
+    numels = [4096, 33, 100_000, 7, 260_000]
+    off, num, n = _layout(numels)
+    nb = len(numels)
+
+    class Side:
+        def __init__(self):
+            g = torch.Generator(device="cuda").manual_seed(11)
+            self.u = torch.zeros(n, device="cuda")
+            self.w = torch.randn(n, device="cuda", generator=g) * 0.02
+            self.v = torch.zeros(n, device="cuda")
+            self.ctx = eb.Context(1, off, num, eb.F32, eb.ORDER_FIXED)
+            self.stats = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+            self.attached = torch.zeros(nb * 4, dtype=torch.float64, device="cuda")
+            nbytes = self.ctx.eager_stats_workspace_bytes()
+            self.ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+            self.nbytes = nbytes
+
+        def calls(self, stream=None):
+            self.ctx.eager_stats_attach(self.attached, self.ws, self.nbytes, stream=stream)
+            self.ctx.eager_sgd_step_lars_static(self.u, (self.w, self.v, 0.1, 0.9), 0.02, self.stats,
+                                                1e-9, stream=stream)
+
+        def load(self, t):
+            g = torch.Generator(device="cuda").manual_seed(100 + t)
+            self.u.copy_(torch.randn(n, device="cuda", generator=g) * 1e-3)
+
+    eager, replayed = Side(), Side()
+    for side in (eager, replayed):
+        side.load(0)
+        side.calls()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        graph.capture_begin()
+        replayed.calls(stream=stream)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(stream)
+    for t in range(1, 5):
+        eager.load(t)
+        replayed.load(t)
+        eager.calls()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(eager.w, replayed.w) and torch.equal(eager.v, replayed.v), t
+        assert torch.equal(eager.stats.view(torch.int64), replayed.stats.view(torch.int64)), t
+        table = replayed.ws[:nb * 16].view(torch.int64).cpu().tolist()
+        assert table == [x for o, m in zip(off, num) for x in (o, o + m)]
+        _ = (eager.w * 2).sum().item()                 # unrelated eager work and a sync
+    eager.ctx.close()
+    replayed.ctx.close()
