@@ -261,6 +261,19 @@ def test_brute_force_with_absent_processes_and_stashes(P, T):
         delivered = np.zeros(n)
         for t in range(T + 1):
             st = seq[t] if t < T else (0,) * P                      # last round: everybody on time
+            if t == T:
+                # the flush (nobody active, everybody absent) on a copy of the state: exactly what
+                # the ledger holds as pending, and every send buffer empty afterwards
+                Rf = [r.copy() for r in R]
+                flushed = np.empty(n, dtype=np.float32)
+                none = [np.full(n, np.nan, dtype=np.float32) for _ in range(P)]     # never read
+                assert eo.round_f32(none, Rf, valid, 0, None, None, 0, 0, flushed,
+                                    absent=(1 << P) - 1) == 0
+                owed = sum(pending, np.zeros(n))
+                if exact:
+                    assert np.array_equal(flushed.astype(np.float64) * P, owed), (seq, "flush")
+                else:
+                    assert np.allclose(flushed.astype(np.float64) * P, owed, rtol=0, atol=1e-5)
             mask = sum(1 << p for p in range(P) if st[p] == 0)
             absent = sum(1 << p for p in range(P) if st[p] == 2)
             G = [grad(t, p, 0) if t < T else np.zeros(n, dtype=np.float32) for p in range(P)]
