@@ -134,17 +134,22 @@ int check_opt(eager_ctx *ctx, const eager_opt *opt)
     return EAGER_OK;
 }
 
+// What becomes of the gradient a late process finishes:
+//   kCopy      it is copied into the send buffer (in the round's pass, or by the copy kernel)
+//   kExchange  its buffer becomes the send buffer: the caller of partial_allreduce exchanges
+//              the two pointers in the user's tables on success, and the round neither reads
+//              nor writes the late gradients
+//   kFlush     there is none: the round in which nobody hands over a gradient (every process
+//              absent, nobody active); `plan` is then a stand-in without an initiator and
+//              belongs to no round index
+enum RoundKind { kCopy, kExchange, kFlush };
+
 // want_mode < 0: any mode.  absent: processes outside the mask that store no gradient.
-// exchange: the gradient buffer of a late process becomes its send buffer by an exchange of the
-// two pointers in the caller's tables (done by the caller of this function on success) instead
-// of a copy: the round then neither reads nor writes the late gradients.
 int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uint64_t absent,
                       int b0, int b1, const void *const *grads, float *const *resid,
-                      float *recv, const eager_opt *opt, void *stream, bool exchange = false,
-                      bool flush = false)
+                      float *recv, const eager_opt *opt, void *stream, RoundKind kind = kCopy)
 {
-    // flush: the round in which nobody hands over a gradient (every process absent, nobody
-    // active): `plan` is a stand-in without an initiator and belongs to no round index
+    const bool exchange = kind == kExchange, flush = kind == kFlush;
     if (!ctx) return EAGER_EINVAL;
     if (!plan || (!grads && !flush) || !resid)
         return fail(ctx, EAGER_EINVAL, "plan, grads and resid must not be NULL");
@@ -516,7 +521,7 @@ int eager_partial_allreduce_exchange(eager_ctx *ctx, const eager_plan *plan, con
         return fail(ctx, EAGER_ESTATE, "a gradient buffer can only become a send buffer when both "
                                        "hold fp32 (this context has bf16 gradients)");
     const int st = partial_allreduce(ctx, -1, plan, 0, 0, ctx->n_buckets, grads, resid, recv, opt,
-                                     stream, true);
+                                     stream, kExchange);
     if (st != EAGER_OK) return st;
     const uint64_t late = ~plan->mask & low_bits(ctx->P);
     for (int p = 0; p < ctx->P; ++p)
@@ -537,7 +542,7 @@ int eager_flush(eager_ctx *ctx, int b0, int b1, float *const *resid, float *recv
     nobody.mode = EAGER_SOLO;
     nobody.P = ctx->P;
     return partial_allreduce(ctx, -1, &nobody, low_bits(ctx->P), b0, b1, nullptr, resid, recv, opt,
-                             stream, false, true);
+                             stream, kFlush);
 }
 
 int eager_stash(eager_ctx *ctx, int process, int b0, int b1, const void *grad, float *resid,

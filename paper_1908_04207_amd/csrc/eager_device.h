@@ -19,7 +19,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 // space, scalar loads).  Going through the by-value parameter instead makes the compiler
 // keep a private copy of the whole struct in scratch memory as soon as it is indexed
 // dynamically in more places than its copy-elision looks at.
-typedef const RoundArgs __attribute__((address_space(4))) KRoundArgs;
 typedef const SlotArgs __attribute__((address_space(4))) KSlotArgs;
 template <typename T>
 __device__ __forceinline__ const T __attribute__((address_space(4))) &kernarg()
@@ -44,18 +43,6 @@ __device__ __forceinline__ u32x4 ld_u4(const void *p)
 {
     if (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
     return *reinterpret_cast<const u32x4 *>(p);
-}
-
-// bf16 is the upper half of an fp32: widening is a shift or a mask, exact.
-__device__ __forceinline__ f32x4 widen_lo(u32x4 x, int half)   // elements 0..3 or 4..7
-{
-    const unsigned a = half ? x.z : x.x, b = half ? x.w : x.y;
-    f32x4 r;
-    r.x = __uint_as_float(a << 16);
-    r.y = __uint_as_float(a & 0xffff0000u);
-    r.z = __uint_as_float(b << 16);
-    r.w = __uint_as_float(b & 0xffff0000u);
-    return r;
 }
 
 // The update rule U of Algorithm 2, lines 7-8, for one element or one vector of 4:

@@ -101,9 +101,9 @@ struct RoundArgs {
     StatsArgs stats;             // stats.stats == NULL: no by-products
 };
 
-// The same round with the streams compacted.  Slot k is one stream and one action; slots are
-// listed in the order in which they enter the sum (ascending rank, send buffer before
-// gradient):
+// The same round as the kernel takes it: a list of streams.  Slot k is one stream and one
+// action; slots are listed in the order in which they enter the sum (ascending rank, send
+// buffer before gradient):
 //   ADD    s = s + x                       (a pending R_p of a late process, or the G_p
 //                                           of an on-time process with an empty buffer)
 //   HOLD   c = x                           (R_p of an on-time process ...)

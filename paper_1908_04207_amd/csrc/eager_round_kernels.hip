@@ -5,7 +5,7 @@
 // The path is a pure stream: per element <= 2P adds, one multiply and two FMAs against
 // >= 4P bytes, so HBM bandwidth is the only roofline that matters and there is no
 // contraction for the matrix cores.  Design for CDNA4:
-//   * slot_kernel (the default): the host compacts the round into a list of streams that
+//   * slot_kernel: the host compacts the round into a list of streams that
 //     must be read, in summation order; a lane owns 4 consecutive elements of every stream,
 //     so a 64-lane wavefront reads or writes one contiguous KiB per fp32 stream and
 //     instruction; the loads of a chunk of 16 streams are all issued before the first add,
@@ -28,10 +28,10 @@
 namespace eager {
 namespace {
 
-// Compacted form: a list of streams ("slots"), each with one action, in summation order.  A
+// The round as a list of streams ("slots"), each with one action, in summation order.  A
 // chunk of C slots is C loads issued back to back, then the adds, then the stores; the list
-// is consumed in chunks of CH and one remainder chunk of its exact size, so that not a
-// single stand-in load is issued.
+// is consumed in chunks of CH and one remainder chunk of its exact size, so that no load is
+// issued for a stream the round does not need.
 //
 // A lane owns 4 consecutive elements of every stream, so that each load or store instruction
 // of a wavefront covers one contiguous kilobyte of an fp32 stream.  With bf16 gradients
