@@ -649,8 +649,8 @@ def test_update_rules_and_views_captured_in_a_graph(eb):
         assert torch.equal(eager.stats.view(torch.int64), replayed.stats.view(torch.int64))
         assert not torch.equal(eager.w[0], eager.w[1])
         _ = (eager.w[0] * 2).sum().item()              # unrelated eager work and a sync
-    # the host state of the replayed side was advanced by the capture only (round 1); the
-    # replays touched no host state, so the library still refuses a second round 1
+    # the host state of the replayed side was advanced by the capture only (to step index 1);
+    # the replays touched no host state, so the library still refuses that step a second time
     with pytest.raises(eb.EagerError):
         replayed.calls(1)
     eager.ctx.close()
