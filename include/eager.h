@@ -214,6 +214,9 @@ int eager_partial_allreduce_quorum(eager_ctx *ctx, const eager_plan *plan, int b
  *                  grads[p] to the former send buffer, whose content has been delivered and which
  *                  is free for the process's next gradient.  Entries of on-time processes stay.
  *                  The caller must use the tables as they come back for every later call.
+ *                  (Under stream capture the pointers are fixed in the graph as they were when
+ *                  the call was captured, like the plan; a replay repeats that one round on
+ *                  those buffers and does not exchange anything again.)
  * Any plan mode is accepted; the range is always every bucket of the context (the exchange of a
  * process's arena pointers concerns all of its buckets).
  * Errors: as eager_partial_allreduce_*; ESTATE also for a context with bf16 gradients.  On an

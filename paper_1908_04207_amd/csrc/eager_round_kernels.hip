@@ -255,7 +255,8 @@ __host__ __device__ __forceinline__ long long slot_nvec(long long n)
 // every slot is loop invariant, the compiler hoists hundreds of them out of it and then
 // spills scalar registers.  The grid always covers the run.  (Two consecutive tiles per
 // wavefront, every stream requested 2 KiB at a time, were measured as well: 3-6 % faster in a
-// plain kernel of 16-34 read and 2 write streams, nothing on the rounds themselves.)
+// plain kernel of 16-34 read and 2 write streams, but on the rounds themselves the same with
+// 18 streams and 2-5 % slower with 13 or 28.)
 template <bool BF16, bool FAST, bool NT, bool NTS, int CH, bool STATS>
 __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
 {

@@ -377,12 +377,16 @@ def test_launch_shapes_give_identical_bits(eb, dtype):
              xcd_map=1),
         dict(block=128, chunk=16, split=1, xcd_map=1),
         dict(block=64, blocks_per_cu=5, split=2, carry_block=64, carry_vec=4)]
+    generated = {}                       # step -> the P gradient arenas (the same for every shape)
     for launch in shapes_:
         pair = Pair(eb, cfg.P, bt.offset, bt.numel, bt.arena_numel, dtype, seed=4)
         for key, val in launch.items():
             pair.ctx.eager_set_launch(key, val)
         for t in range(3):
-            pair.round(plan_for(eb, cfg, t), pair.fresh_grads(t))
+            if t not in generated:
+                generated[t] = [wg.fill(torch.empty(pair.arena, dtype=pair.dtype), pair.seed, t, p,
+                                        pair.gs) for p in range(cfg.P)]
+            pair.round(plan_for(eb, cfg, t), pair.set_grads(generated[t]))
         pair.compare(exact=True, what=f"launch {launch}")
         torch.cuda.synchronize()
         if ref is None:
