@@ -120,6 +120,64 @@ def test_full_size_sampled(eb, k, steps, order, launch):
     ctx.close()
 
 
+@pytest.mark.parametrize("k,steps", [(3, 4), (4, 3)])
+def test_full_size_exchange_rounds_then_flush(eb, k, steps):
+    """The round that the benchmark also times without the copy: a late gradient's buffer takes
+    the send buffer's role (the binding permutes G and R as the library does the tables), and
+    at the end the round in which nobody hands over a gradient delivers what is pending.
+    Same sample, same oracle rounds (the oracle knows only the copying round), bit for bit."""
+    cfg = shapes.config(k)
+    bt = cfg.buckets
+    dev = torch.device("cuda:0")
+    n = bt.arena_numel
+    S = sample_indices(cfg)
+    S_t = torch.from_numpy(S)
+    S_dev = S_t.to(dev)
+    ctx = eb.Context(cfg.P, bt.offset, bt.numel, eb.F32, eb.ORDER_FIXED)
+    G = [torch.empty(n, device=dev) for _ in range(cfg.P)]
+    R = [torch.empty(n, device=dev) for _ in range(cfg.P)]
+    w = wg.fill(torch.empty(n, device=dev), cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma)
+    v = torch.zeros(n, device=dev)
+    recv = torch.empty(n, device=dev)
+    w0 = wg.values_at(S_t, cfg.seed, 0, wg.PARAM_RANK, cfg.param_sigma).numpy()
+    oracle = eo.OracleState(cfg.P, [0], [len(S)], len(S), w0, cfg.lr, cfg.mu)
+    oracle_recv = np.zeros(len(S), dtype=np.float32)
+
+    def check(what, with_recv=False):
+        torch.cuda.synchronize()
+        valid = ctx.eager_get_valid(0)
+        assert all(ctx.eager_get_valid(b) == valid for b in range(bt.n_buckets))
+        assert valid == oracle.valid[0]
+        got = {"w": w[S_dev].cpu().numpy(), "v": v[S_dev].cpu().numpy()}
+        want = {"w": oracle.w, "v": oracle.v}
+        if with_recv:
+            got["recv"], want["recv"] = recv[S_dev].cpu().numpy(), oracle_recv
+        for p in range(cfg.P):
+            if (valid >> p) & 1:
+                got[f"R{p}"], want[f"R{p}"] = R[p][S_dev].cpu().numpy(), oracle.R[p]
+        for name in got:
+            assert np.array_equal(bits(got[name]), bits(want[name])), f"{cfg.name} {what}: {name}"
+        return valid
+
+    for t in range(steps):
+        print(f"{cfg.name} exchange round, step {t}", flush=True)
+        plan = plan_for(eb, cfg, t)
+        for p in range(cfg.P):
+            wg.fill(G[p], cfg.seed, t, p, cfg.grad_sigma)      # whichever buffer is G_p now
+        ctx.eager_partial_allreduce_exchange(plan, G, R, opt=(w, v, cfg.lr, cfg.mu))
+        Gs = [as_oracle_grad(wg.grad_at(S_t, cfg.seed, t, p, cfg.grad_sigma, torch.float32))
+              for p in range(cfg.P)]
+        oracle.round(plan.mask, Gs)
+        check(f"step {t}")
+    assert len({x.data_ptr() for x in G + R}) == 2 * cfg.P      # still 2P distinct buffers
+    print(f"{cfg.name} flush", flush=True)
+    ctx.eager_flush(R, recv=recv, opt=(w, v, cfg.lr, cfg.mu))
+    nothing = [np.zeros(len(S), dtype=np.float32) for _ in range(cfg.P)]
+    oracle.round(0, nothing, recv=oracle_recv, absent=(1 << cfg.P) - 1)
+    assert check("flush", with_recv=True) == 0
+    ctx.close()
+
+
 @pytest.mark.parametrize("k", [2, 3])
 def test_full_size_bucket_statistics(eb, k):
     """The per-bucket sums at full size (hundreds of thousands of wavefront records, buckets
