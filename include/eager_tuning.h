@@ -18,12 +18,12 @@ extern "C" {
 /*
  * Launch shape of the round kernels of a context.  Unknown keys and values outside the listed
  * ones: EINVAL.  Every combination of listed values has a kernel.
- *   "split"      0 = chosen per round (default): with fp32 gradients the send-buffer rewrite of
- *                the late processes runs as a copy kernel of its own after the reduction when
- *                somebody is late and the fused pass would read more than 16 streams, when 8 or
- *                more processes are late, or when 3 or more are late and the run has 2^25
- *                elements or more; with bf16 gradients never.  1 = always one fused kernel;
- *                2 = always reduction + update kernel followed by the copy kernel
+ *   "split"      0 = chosen per round (default): the send-buffer rewrite of the late
+ *                processes runs as a copy kernel of its own after the reduction when somebody
+ *                is late and the fused pass would read more than 16 streams, when 8 or more
+ *                processes are late, or when 3 or more are late and the run has 2^25 elements
+ *                or more.  1 = always one fused kernel; 2 = always reduction + update kernel
+ *                followed by the copy kernel
  *   "chunk"      streams whose loads are in flight together per wavefront: 0 (default) = 16, 8, 16.
  *                Per-bucket statistics need 16
  *   "block"      threads per workgroup: 64 (default), 128 or 256

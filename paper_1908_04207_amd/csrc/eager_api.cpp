@@ -96,8 +96,7 @@ int stats_slices(const eager_ctx *ctx, int b0, int b1)
 
 // Whether the send-buffer rewrite of the late processes runs as its own copy kernel after
 // the reduction instead of inside it.
-bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t valid,
-               int64_t n)
+bool use_split(const eager::Launch &l, int P, uint64_t mask, uint64_t valid, int64_t n)
 {
     if (l.split == 1) return false;
     if (l.split == 2) return true;
@@ -106,10 +105,9 @@ bool use_split(const eager::Launch &l, bool bf16, int P, uint64_t mask, uint64_t
     // to the reduction's reads cost 5-10 % of the round (P = 8, 7 late: 6.1 fused, 6.7 split).
     // The fused pass wins while few processes are late and all of its streams fit one chunk
     // of 16 loads, and on short runs, where the second launch costs more than it saves
-    // (25 M elements, P = 8: 7.03 fused against 6.82 TB/s split).  With bf16 gradients the
-    // fused pass is the faster one as well (6.37 against 6.28 TB/s on the 1.5 B-parameter
-    // configuration).
-    if (bf16) return false;
+    // (25 M elements, P = 8: 7.03 fused against 6.82 TB/s split).  The same holds with bf16
+    // gradients (P = 16, 15 late: 6.43 split against 5.91 TB/s fused on 67 M elements, 6.31
+    // against 6.19 on 1.56e9; P = 16, 2 late, 16 M elements: 6.68 split against 6.71 fused).
     const uint64_t late = ~mask & low_bits(P);
     const int n_late = popcount64(late);
     if (n_late == 0) return false;
@@ -244,7 +242,7 @@ int partial_allreduce(eager_ctx *ctx, int want_mode, const eager_plan *plan, uin
         a.n = ctx->offset[e - 1] + ctx->numel[e - 1] - ctx->offset[b];
         const uint64_t late = ~plan->mask & ~absent & low_bits(P);   // finish a gradient late
         const bool split = exchange ||
-                           use_split(ctx->launch, ctx->bf16, P, plan->mask | absent, a.valid, a.n);
+                           use_split(ctx->launch, P, plan->mask | absent, a.valid, a.n);
         a.gload = split ? plan->mask : (plan->mask | late);
         a.store = split ? 0 : late;
         if (round_stats) {

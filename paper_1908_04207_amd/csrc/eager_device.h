@@ -231,7 +231,7 @@ constexpr long long kMaxGridThreads = 1ll << 31;
 constexpr long long kStateCacheBytes = 256ll << 20;
 
 template <typename K, typename A, typename... Extra>
-hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, unsigned grid,
+hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, dim3 grid,
                          hipStream_t st, Extra... extra)
 {
     unsigned lds = 0;
@@ -251,7 +251,7 @@ hipError_t launch_capped(K kernel, const A &a, int bpc, const Launch &cfg, unsig
             raised.insert(fn);
         }
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(cfg.block), lds, st, a, extra...);
+    hipLaunchKernelGGL(kernel, grid, dim3(cfg.block), lds, st, a, extra...);
     return hipGetLastError();
 }
 

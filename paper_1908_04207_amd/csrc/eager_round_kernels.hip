@@ -25,6 +25,8 @@
 //     them in eager_aux_kernels.hip).
 #include "eager_device.h"
 
+#include <algorithm>
+
 namespace eager {
 namespace {
 
@@ -304,51 +306,49 @@ __global__ __launch_bounds__(256) void slot_kernel(const SlotArgs)
         slot_scalar<BF16, STATS>(a, a.e0 + nvec * 4 + threadIdx.x);
 }
 
-// R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx is
-// pair-major), so that at any time the device streams one source and one destination.
-// A copy of few streams runs near the read-only rate on MI355X, whereas the same bytes
-// written as 8-31 interleaved streams next to the reduction's reads cost 10-15 %.
-// A lane owns 4 elements: every store instruction of a wavefront writes one contiguous
-// kilobyte (a bf16 source is read 8 bytes per lane and widened).
+// R_p <- G_p for the late processes, as a plain copy: pair after pair (blockIdx.y is the
+// pair, and workgroups are dealt out x first), so that at any time the device streams one
+// source and one destination.  A copy of few streams runs near the read-only rate on MI355X,
+// whereas the same bytes written as 8-31 interleaved streams next to the reduction's reads
+// cost 10-15 %.  A lane owns 4 elements: every store instruction of a wavefront writes one
+// contiguous kilobyte (a bf16 source is read 8 bytes per lane and widened).  No loop and no
+// division: a wavefront lives for one load and one store, so whatever stands before its load
+// counts (bf16 source, 1.1e9 elements per pair: 6.73 TB/s in this form, 6.62 with the pair
+// taken from blockIdx.x by a division, 6.46 with a striding loop around the body).
 template <bool BF16, int V>
-__global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a, unsigned blocks_per_pair)
+__global__ __launch_bounds__(256) void carry_kernel(const CarryArgs a)
 {
-    const unsigned pair = blockIdx.x / blocks_per_pair;
-    const unsigned blk = blockIdx.x - pair * blocks_per_pair;
+    const unsigned pair = blockIdx.y;
     const long long nvec = a.n / 4;
     const char *src = static_cast<const char *>(a.src[pair]);
     float *dst = a.dst[pair];
-    // a workgroup copies V * blockDim consecutive lane-vectors per iteration: all loads
-    // first, then the stores
-    const long long tile = static_cast<long long>(blockDim.x) * V;
-    for (long long base = static_cast<long long>(blk) * tile; base < nvec;
-         base += static_cast<long long>(blocks_per_pair) * tile) {
-        f32x4 x[V];
+    // a workgroup copies V * blockDim consecutive lane-vectors: all loads first, then the stores
+    const long long base = static_cast<long long>(blockIdx.x) * blockDim.x * V + threadIdx.x;
+    f32x4 x[V];
 #pragma unroll
-        for (int k = 0; k < V; ++k) {
-            const long long vi = base + static_cast<long long>(k) * blockDim.x + threadIdx.x;
-            if (vi < nvec) {
-                const long long e = a.e0 + vi * 4;
-                if (BF16) {
-                    const u32x2 g = __builtin_nontemporal_load(
-                        reinterpret_cast<const u32x2 *>(src + e * 2));
-                    x[k].x = __uint_as_float(g.x << 16);
-                    x[k].y = __uint_as_float(g.x & 0xffff0000u);
-                    x[k].z = __uint_as_float(g.y << 16);
-                    x[k].w = __uint_as_float(g.y & 0xffff0000u);
-                } else {
-                    x[k] = ld_f4<true>(reinterpret_cast<const float *>(src + e * 4));
-                }
+    for (int k = 0; k < V; ++k) {
+        const long long vi = base + static_cast<long long>(k) * blockDim.x;
+        if (vi < nvec) {
+            const long long e = a.e0 + vi * 4;
+            if (BF16) {
+                const u32x2 g = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x2 *>(src + e * 2));
+                x[k].x = __uint_as_float(g.x << 16);
+                x[k].y = __uint_as_float(g.x & 0xffff0000u);
+                x[k].z = __uint_as_float(g.y << 16);
+                x[k].w = __uint_as_float(g.y & 0xffff0000u);
+            } else {
+                x[k] = ld_f4<true>(reinterpret_cast<const float *>(src + e * 4));
             }
         }
+    }
 #pragma unroll
-        for (int k = 0; k < V; ++k) {
-            const long long vi = base + static_cast<long long>(k) * blockDim.x + threadIdx.x;
-            if (vi < nvec) st_f4<true>(dst + a.e0 + vi * 4, x[k]);
-        }
+    for (int k = 0; k < V; ++k) {
+        const long long vi = base + static_cast<long long>(k) * blockDim.x;
+        if (vi < nvec) st_f4<true>(dst + a.e0 + vi * 4, x[k]);
     }
     const long long rem = a.n - nvec * 4;
-    if (blk == 0 && static_cast<long long>(threadIdx.x) < rem) {
+    if (blockIdx.x == 0 && static_cast<long long>(threadIdx.x) < rem) {
         const long long i = a.e0 + nvec * 4 + threadIdx.x;
         dst[i] = load_grad_scalar<BF16>(src, i);
     }
@@ -405,11 +405,19 @@ void build_slots(const RoundArgs &a, SlotArgs &s)
 int auto_waves_for_slots(const SlotArgs &s, bool has_stores)
 {
     const int n = s.n_slots;
-    const int base = has_stores ? (n <= 16 ? 8 : 5) : (n <= 20 ? 10 : 5);
     const int n_bf = __builtin_popcountll(s.bf[0]) + __builtin_popcountll(s.bf[1]);
-    // (one chunk with stores: the stores are full-width fp32 whatever the gradient type, and
-    // 8 stays the best count - P = 8, bf16, majority: 6.46 against 6.23 TB/s with 12)
-    if (n_bf == 0 || n == 0 || (has_stores && n <= 16)) return base;
+    if (has_stores && n <= 16) {
+        // One chunk with stores: about 84 KiB of loads in flight per CU, between 8 and 12
+        // wavefronts.  A wavefront requests a KiB per fp32 stream (w and v included), half of
+        // that per bf16 stream.  Measured, 2e8 elements: 3 fp32 streams 6.64 TB/s with 12
+        // against 6.17 with 8; 4 bf16 + 1 fp32 streams 6.64 against 5.72; 8 bf16 + 1 fp32
+        // (2.6e7 elements) 6.94 against 6.43; from 9 fp32 streams on 8 stays the best count.
+        const int half_kib = 2 * (n - n_bf) + n_bf + 4;
+        const int waves = (2 * 84 + half_kib / 2) / half_kib;
+        return waves < 8 ? 8 : waves > 12 ? 12 : waves;
+    }
+    const int base = has_stores ? 5 : (n <= 20 ? 10 : 5);
+    if (n_bf == 0 || n == 0) return base;
     // base / (1 - share/2), rounded
     const int waves = (2 * base * n + (2 * n - n_bf) / 2) / (2 * n - n_bf);
     return waves > 16 ? 16 : waves;
@@ -484,16 +492,29 @@ hipError_t launch_carry_v(const CarryArgs &a, const Launch &cfg, hipStream_t str
 {
     const long long nvec = a.n / 4;
     const long long tile = static_cast<long long>(cfg.carry_block) * V;
-    long long bpp = (nvec + tile - 1) / tile;
+    long long bpp = (nvec + tile - 1) / tile;     // workgroups per pair: they cover it
     if (bpp < 1) bpp = 1;
-    // a grid may hold fewer than 2^32 threads in all; beyond that the kernel strides
-    const long long cap = kMaxGridThreads / cfg.carry_block / a.count;
-    if (bpp > cap) bpp = cap;
-    const unsigned grid = static_cast<unsigned>(bpp) * static_cast<unsigned>(a.count);
+    // A grid may hold fewer than 2^32 threads in all: the pairs go into as many launches as it
+    // takes.  (One pair always fits: a call covers at most 2^33 elements per run.)
+    const long long limit = kMaxGridThreads / cfg.carry_block;
+    if (bpp > limit) return hipErrorInvalidValue;
+    long long pairs_per_launch = std::min<long long>(limit / bpp, 65535);
     Launch l = cfg;
     l.block = cfg.carry_block;
-    return launch_capped(carry_kernel<BF16, V>, a, cfg.carry_blocks_per_cu, l, grid, stream,
-                         static_cast<unsigned>(bpp));
+    for (int first = 0; first < a.count; first += static_cast<int>(pairs_per_launch)) {
+        CarryArgs part = a;
+        part.count = static_cast<int>(std::min<long long>(pairs_per_launch, a.count - first));
+        for (int k = 0; k < part.count; ++k) {
+            part.src[k] = a.src[first + k];
+            part.dst[k] = a.dst[first + k];
+        }
+        const hipError_t e = launch_capped(carry_kernel<BF16, V>, part, cfg.carry_blocks_per_cu, l,
+                                           dim3(static_cast<unsigned>(bpp),
+                                                static_cast<unsigned>(part.count)),
+                                           stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 template <bool BF16>
